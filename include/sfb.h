@@ -1,0 +1,182 @@
+/*
+ * sfb.h -- C ABI of the MI355X (gfx950) library for the data-parallel hot path of
+ * Sufficient Factor Broadcasting (SFB).
+ *
+ * One bulk-synchronous SFB iteration for a matrix-parametrised model
+ *     min_W (1/N) sum_i f_i(W a_i) + h(W),   W in R^{J x D}          (Section 2, problem (P))
+ * on P simulated workers that each hold B samples of the minibatch and an identical
+ * replica of W (Section 3; replicas are equal under BSP, Section 4.1):
+ *
+ *   factors      u_i = d f_i(W a_i) / d (W a_i),  v_i = a_i            (Section 2.1, proximal SGD)
+ *   exchange     worker p's B pairs land in rows [p*B, (p+1)*B) of the concatenated
+ *                buffers U[N][J], V[N][D], N = P*B: what every worker holds once all
+ *                broadcasts have arrived                                (Section 3)
+ *   reconstruct  dW = sum_p (1/B) sum_i u_{p,i} v_{p,i}^T               (Section 3, sum over
+ *                workers; mini-batch paragraph, mean over a worker's K = B samples)
+ *   apply        W <- W - eta * dW; prox is the identity (h = 0)        (Section 2.1)
+ *
+ * Conventions that hold for every entry point:
+ *   - Every matrix is ROW-MAJOR with an explicit leading dimension counted in ELEMENTS.
+ *   - Every data pointer (W, features, labels, U, V, loss, workspace) is DEVICE memory owned
+ *     by the caller.  The library allocates and frees no device memory and keeps no data
+ *     pointer after a call returns, except the workspace registered with sfb_set_workspace.
+ *     The only HOST data pointer is the `active` mask.  Struct arguments (sfb_batch) live on
+ *     the host and are read during the call only.
+ *   - Calls enqueue kernels on the context's HIP stream and return without synchronising.
+ *     A launch failure is returned at once as SFB_EHIP; a fault during execution surfaces
+ *     at sfb_sync or at the next call.
+ *   - Errors are reported by the integer return value only.  If validation fails no kernel
+ *     is launched and no output is touched.
+ *   - Any alignment and any leading dimension >= the row length is accepted; pointers that
+ *     are 16-byte aligned with leading dimensions that are multiples of 4 elements (8 for
+ *     bf16) take the vectorised paths.
+ *   - Class ids in `y` outside [0, J) are not detected on the device (the one-hot term is
+ *     then simply absent); callers validate labels.
+ *   - A context is not thread-safe; distinct contexts are independent.
+ */
+#ifndef SFB_H
+#define SFB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SFB_API __attribute__((visibility("default")))
+
+typedef struct sfb_ctx sfb_ctx; /* opaque, host-side dispatch state only */
+
+/* Loss families (f_i of problem (P), Section 2). */
+typedef enum {
+    SFB_MLR = 0,   /* multiclass logistic: f = logsumexp(z) - z_y; u = softmax(z) - e_y          */
+    SFB_DML = 1,   /* distance metric learning: a = x - y (pair difference), z = W a;
+                      similar pair f = |z|^2, u = 2z; dissimilar f = max(0, 1 - |z|^2),
+                      u = -2z if |z|^2 < 1 else 0 (Section 2, DML paragraph)                     */
+    SFB_L2SVM = 2  /* one-vs-rest squared hinge, t_j = +1 if j == y else -1:
+                      f = sum_j max(0, 1 - t_j z_j)^2, u_j = -2 t_j max(0, 1 - t_j z_j);
+                      features given as CSR                                                      */
+} sfb_model;
+
+/* Storage type of the features and of V.  W, U, loss and the workspace are always fp32. */
+typedef enum { SFB_F32 = 0, SFB_BF16 = 1 } sfb_dtype;
+
+typedef enum {
+    SFB_OK = 0,
+    SFB_EINVAL = -1,       /* null pointer, non-positive size, non-finite eta or scale      */
+    SFB_ESHAPE = -2,       /* leading dimension shorter than the row, nnz < 0, p out of range */
+    SFB_EDTYPE = -3,       /* unknown dtype                                                  */
+    SFB_EWORKSPACE = -5,   /* workspace missing or smaller than sfb_workspace_bytes          */
+    SFB_EUNSUPPORTED = -6, /* (model, dtype) combination or size the kernels do not cover    */
+    SFB_EHIP = -7          /* a HIP call failed; see sfb_last_hip_error                      */
+} sfb_status;
+
+/*
+ * One minibatch, already laid out as P contiguous partitions of B samples (worker p's draw
+ * is rows [p*B, (p+1)*B)).  Host struct of DEVICE pointers.
+ *   MLR:    a = features [N][lda] in the context's dtype; a2 = csr_* = NULL.
+ *   DML:    a = first point of each pair, a2 = second point, both [N][lda] (fp32 only).
+ *   L2SVM:  a = a2 = NULL; CSR with N rows and D columns: csr_rowptr [N+1] (int32, first
+ *           entry is this batch's offset into csr_col/csr_val, normally 0), csr_col [nnz]
+ *           in [0, D), csr_val [nnz] fp32, nnz = total stored entries.  Columns may appear
+ *           in any order; a column repeated inside a row is not supported.
+ */
+typedef struct sfb_batch {
+    const void *a;
+    const void *a2;
+    int64_t lda;
+    const int32_t *csr_rowptr;
+    const int32_t *csr_col;
+    const float *csr_val;
+    int64_t nnz;
+} sfb_batch;
+
+/*
+ * Create a context for model `m`, W of J x D, P workers x B samples, feature storage type
+ * `input_dtype`, enqueueing on `hip_stream` (a hipStream_t; NULL = the default stream).
+ * Mirrors the paper's constructor sfb_app(J, D, staleness) (Section 4.2) without staleness:
+ * only the bulk-synchronous mode exists here.
+ */
+SFB_API sfb_status sfb_create(sfb_ctx **out, sfb_model m, int64_t J, int64_t D, int32_t P, int32_t B,
+                      sfb_dtype input_dtype, void *hip_stream);
+SFB_API void sfb_destroy(sfb_ctx *ctx);
+
+/* Bytes of device workspace the factor computation needs (scores Z[N][J] as split-K
+ * partial sums).  The caller allocates at least that many bytes, 16-byte aligned, and
+ * registers them; the library uses the buffer until it is replaced or the ctx destroyed. */
+SFB_API sfb_status sfb_workspace_bytes(const sfb_ctx *ctx, size_t *bytes);
+SFB_API sfb_status sfb_set_workspace(sfb_ctx *ctx, void *dev, size_t bytes);
+
+/*
+ * Factors of all N = P*B samples, every sample differentiated at the same W
+ * (Section 2.1; Section 4.2: write_u / write_v / commit of every worker).
+ *   W     [J][ldw] fp32, read only.
+ *   y     [N] int32: class id (MLR, L2SVM) or 1 = similar / 0 = dissimilar (DML).
+ *   U     [N][ldu] fp32 out: u_i, unscaled (MLR rows sum to 0).
+ *   V     [N][ldv] out, context dtype: v_i = a_i (DML: x_i - y_i; L2SVM: the dense row).
+ *   loss  [N] fp32 out or NULL: f_i(W a_i).
+ */
+SFB_API sfb_status sfb_compute_factors(sfb_ctx *ctx, const float *W, int64_t ldw, const sfb_batch *batch,
+                               const int32_t *y, float *U, int64_t ldu, void *V, int64_t ldv,
+                               float *loss);
+
+/*
+ * One worker's share: `batch_p` and `y_p` hold that worker's B samples only (B rows; CSR with
+ * B rows); the call writes rows [p*B, (p+1)*B) of U, V (and loss) and nothing else -- one
+ * worker's commit() into slot p of everybody's receive buffer (Section 4.2, Section 3).
+ * U, V, loss are the base pointers of the full N-row buffers.
+ */
+SFB_API sfb_status sfb_compute_factors_worker(sfb_ctx *ctx, const float *W, int64_t ldw,
+                                      const sfb_batch *batch_p, const int32_t *y_p, int32_t p,
+                                      float *U, int64_t ldu, void *V, int64_t ldv, float *loss);
+
+/*
+ * W <- W - eta * scale * sum over live workers p, samples i of u_{p,i} v_{p,i}^T, in place
+ * (Section 3 reconstruction fused with the Section 2.1 update).  scale = 1/B gives the
+ * mini-batch mean of Section 3; scale = 1 the plain sum.  `active` is a HOST array of P
+ * bytes (0 = that worker's factors never arrived, cf. Section 4.4) or NULL for all live;
+ * with a mask P must be <= 64.  U and V are not modified.
+ */
+SFB_API sfb_status sfb_reconstruct_apply(sfb_ctx *ctx, float *W, int64_t ldw, const float *U, int64_t ldu,
+                                 const void *V, int64_t ldv, float eta, float scale,
+                                 const uint8_t *active);
+
+/* sfb_compute_factors followed by sfb_reconstruct_apply with scale = 1/B: one full BSP
+ * iteration.  U, V (and loss) hold the step's factors afterwards. */
+SFB_API sfb_status sfb_step(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_batch *batch, const int32_t *y,
+                    float *U, int64_t ldu, void *V, int64_t ldv, float *loss, float eta,
+                    const uint8_t *active);
+
+/* hipStreamSynchronize on the context's stream; SFB_EHIP if the stream reports an error. */
+SFB_API sfb_status sfb_sync(sfb_ctx *ctx);
+
+/* Static description of a status code. */
+SFB_API const char *sfb_strerror(sfb_status s);
+/* Last hipError_t seen by this context (0 = hipSuccess). */
+SFB_API int sfb_last_hip_error(const sfb_ctx *ctx);
+
+/*
+ * Read back the launch plan chosen at creation (for benches and tests): number of split-K
+ * slices of the score contraction, and the elapsed-time bookkeeping switch.  When timing is
+ * enabled every launch is bracketed by HIP events on the context's stream; sfb_kernel_time_ms
+ * synchronises and returns the accumulated milliseconds and launch count of kernel family
+ * `which` (0 = scores, 1 = factor u, 2 = reconstruct-apply, 3 = sparse helpers) since the
+ * last reset.
+ */
+SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32_t *fwd_grid,
+                         int32_t *recon_grid);
+/* Tuning override of the launch plan: forward tile (bm, bn in {64, 128}), split-K slices,
+ * reconstruct tile variant (0: 128x128, 1: 64x128, 2: 32x128, 3: 256x128 rows x columns of W).
+ * A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
+ * query sfb_workspace_bytes again.  SFB_EINVAL for a value outside the table. */
+SFB_API sfb_status sfb_set_plan(sfb_ctx *ctx, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k,
+                                int32_t recon_variant);
+SFB_API sfb_status sfb_enable_timing(sfb_ctx *ctx, int enable);
+SFB_API sfb_status sfb_kernel_time_ms(sfb_ctx *ctx, int which, double *ms, int64_t *launches);
+SFB_API sfb_status sfb_reset_timing(sfb_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SFB_H */

@@ -1,0 +1,213 @@
+"""ctypes binding of libsfb.so.  Argument marshalling only: every step of the path runs in
+the library's kernels.  Tensors are torch CUDA tensors used as plain device buffers
+(data_ptr + row stride); torch does no arithmetic here."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+SFB_MLR, SFB_DML, SFB_L2SVM = 0, 1, 2
+SFB_F32, SFB_BF16 = 0, 1
+_MODELS = {"mlr": SFB_MLR, "dml": SFB_DML, "l2svm": SFB_L2SVM}
+_DTYPES = {"f32": SFB_F32, "bf16": SFB_BF16}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def library_path():
+    return os.path.join(_HERE, "libsfb.so")
+
+
+class sfb_batch(C.Structure):
+    _fields_ = [("a", C.c_void_p), ("a2", C.c_void_p), ("lda", C.c_int64),
+                ("csr_rowptr", C.c_void_p), ("csr_col", C.c_void_p), ("csr_val", C.c_void_p),
+                ("nnz", C.c_int64)]
+
+
+def _load():
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_1511_08486_amd.build` "
+                          "(there is no fallback path)")
+    try:
+        lib = C.CDLL(path)
+    except OSError as e:  # pragma: no cover
+        raise ImportError(f"cannot load {path}: {e}") from e
+    vp, i64, i32, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_float
+    pb = C.POINTER(sfb_batch)
+    sigs = {
+        "sfb_create": (C.c_int, [C.POINTER(vp), C.c_int, i64, i64, i32, i32, C.c_int, vp]),
+        "sfb_destroy": (None, [vp]),
+        "sfb_workspace_bytes": (C.c_int, [vp, C.POINTER(C.c_size_t)]),
+        "sfb_set_workspace": (C.c_int, [vp, vp, C.c_size_t]),
+        "sfb_compute_factors": (C.c_int, [vp, vp, i64, pb, vp, vp, i64, vp, i64, vp]),
+        "sfb_compute_factors_worker": (C.c_int, [vp, vp, i64, pb, vp, i32, vp, i64, vp, i64, vp]),
+        "sfb_reconstruct_apply": (C.c_int, [vp, vp, i64, vp, i64, vp, i64, f32, f32, vp]),
+        "sfb_step": (C.c_int, [vp, vp, i64, pb, vp, vp, i64, vp, i64, vp, f32, vp]),
+        "sfb_sync": (C.c_int, [vp]),
+        "sfb_strerror": (C.c_char_p, [C.c_int]),
+        "sfb_last_hip_error": (C.c_int, [vp]),
+        "sfb_plan_info": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
+        "sfb_set_plan": (C.c_int, [vp, i32, i32, i32, i32]),
+        "sfb_enable_timing": (C.c_int, [vp, C.c_int]),
+        "sfb_kernel_time_ms": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
+        "sfb_reset_timing": (C.c_int, [vp]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)          # AttributeError here = the library lacks a declared symbol
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+lib = _load()
+
+
+def sfb_strerror(status):
+    return lib.sfb_strerror(int(status)).decode()
+
+
+class SfbError(RuntimeError):
+    def __init__(self, status, where, hip=0):
+        self.status, self.hip = int(status), int(hip)
+        super().__init__(f"{where}: {sfb_strerror(status)} (status {int(status)}, hip error {int(hip)})")
+
+
+class SfbBatch:
+    """One minibatch as device tensors.  Dense: a [N, D] (and a2 for DML pairs).
+    Sparse (L2-SVM): rowptr int32 [N+1], col int32 [nnz], val float32 [nnz]."""
+
+    def __init__(self, a=None, a2=None, rowptr=None, col=None, val=None):
+        self.a, self.a2, self.rowptr, self.col, self.val = a, a2, rowptr, col, val
+
+    def c_struct(self):
+        s = sfb_batch()
+        if self.a is not None:
+            s.a, s.lda = self.a.data_ptr(), self.a.stride(0)
+        if self.a2 is not None:
+            s.a2 = self.a2.data_ptr()
+            if self.a is not None and self.a2.stride(0) != self.a.stride(0):
+                raise ValueError("a and a2 must share their row stride")
+        if self.rowptr is not None:
+            s.csr_rowptr = self.rowptr.data_ptr()
+            s.csr_col = self.col.data_ptr() if self.col is not None and self.col.numel() else None
+            s.csr_val = self.val.data_ptr() if self.val is not None and self.val.numel() else None
+            s.nnz = int(self.col.numel()) if self.col is not None else 0
+        return s
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+class Sfb:
+    """Owns one sfb_ctx plus its workspace; methods mirror the C entry points."""
+
+    def __init__(self, model, J, D, P, B, dtype="f32", stream=None, device="cuda:0"):
+        self.model = _MODELS[model] if isinstance(model, str) else int(model)
+        self.dtype = _DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
+        self.J, self.D, self.P, self.B = int(J), int(D), int(P), int(B)
+        self.device = torch.device(device)
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+        self.stream = int(stream)
+        self._ctx = C.c_void_p()
+        self._check(lib.sfb_create(C.byref(self._ctx), self.model, self.J, self.D, self.P, self.B,
+                                   self.dtype, C.c_void_p(self.stream)), "sfb_create")
+        self._ws = None
+        self._ensure_workspace()
+
+    # -- plumbing ---------------------------------------------------------
+    def _check(self, status, where):
+        if status != 0:
+            hip = lib.sfb_last_hip_error(self._ctx) if self._ctx else 0
+            raise SfbError(status, where, hip)
+
+    def _ensure_workspace(self):
+        need = C.c_size_t()
+        self._check(lib.sfb_workspace_bytes(self._ctx, C.byref(need)), "sfb_workspace_bytes")
+        if self._ws is None or self._ws.numel() < need.value:
+            self._ws = torch.empty(max(int(need.value), 16), dtype=torch.uint8, device=self.device)
+        self._check(lib.sfb_set_workspace(self._ctx, self._ws.data_ptr(), self._ws.numel()),
+                    "sfb_set_workspace")
+
+    def close(self):
+        if getattr(self, "_ctx", None):
+            lib.sfb_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace_bytes(self):
+        need = C.c_size_t()
+        self._check(lib.sfb_workspace_bytes(self._ctx, C.byref(need)), "sfb_workspace_bytes")
+        return int(need.value)
+
+    # -- the path -----------------------------------------------------------
+    def compute_factors(self, W, batch, y, U, V, loss=None):
+        b = batch.c_struct()
+        self._check(lib.sfb_compute_factors(self._ctx, W.data_ptr(), W.stride(0), C.byref(b), y.data_ptr(),
+                                            U.data_ptr(), U.stride(0), V.data_ptr(), V.stride(0),
+                                            _ptr(loss)), "sfb_compute_factors")
+
+    def compute_factors_worker(self, W, batch_p, y_p, p, U, V, loss=None):
+        b = batch_p.c_struct()
+        self._check(lib.sfb_compute_factors_worker(self._ctx, W.data_ptr(), W.stride(0), C.byref(b),
+                                                   y_p.data_ptr(), int(p), U.data_ptr(), U.stride(0),
+                                                   V.data_ptr(), V.stride(0), _ptr(loss)),
+                    "sfb_compute_factors_worker")
+
+    @staticmethod
+    def _mask(active):
+        if active is None:
+            return None, None
+        buf = (C.c_uint8 * len(active))(*[1 if a else 0 for a in active])
+        return buf, C.cast(buf, C.c_void_p)
+
+    def reconstruct_apply(self, W, U, V, eta, scale=None, active=None):
+        if scale is None:
+            scale = 1.0 / self.B
+        if active is not None and len(active) != self.P:
+            raise ValueError("active mask must have P entries")
+        keep, ptr = self._mask(active)
+        self._check(lib.sfb_reconstruct_apply(self._ctx, W.data_ptr(), W.stride(0), U.data_ptr(), U.stride(0),
+                                              V.data_ptr(), V.stride(0), float(eta), float(scale), ptr),
+                    "sfb_reconstruct_apply")
+
+    def step(self, W, batch, y, U, V, eta, loss=None, active=None):
+        if active is not None and len(active) != self.P:
+            raise ValueError("active mask must have P entries")
+        b = batch.c_struct()
+        keep, ptr = self._mask(active)
+        self._check(lib.sfb_step(self._ctx, W.data_ptr(), W.stride(0), C.byref(b), y.data_ptr(), U.data_ptr(),
+                                 U.stride(0), V.data_ptr(), V.stride(0), _ptr(loss), float(eta), ptr),
+                    "sfb_step")
+
+    def sync(self):
+        self._check(lib.sfb_sync(self._ctx), "sfb_sync")
+
+    # -- plan / timing -------------------------------------------------------
+    def plan_info(self):
+        a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+        self._check(lib.sfb_plan_info(self._ctx, C.byref(a), C.byref(b), C.byref(c)), "sfb_plan_info")
+        return {"fwd_split_k": a.value, "fwd_grid": b.value, "recon_grid": c.value}
+
+    def set_plan(self, fwd_bm=0, fwd_bn=0, fwd_split_k=0, recon_variant=-1):
+        self._check(lib.sfb_set_plan(self._ctx, fwd_bm, fwd_bn, fwd_split_k, recon_variant), "sfb_set_plan")
+        self._ensure_workspace()
+
+    def enable_timing(self, on=True):
+        self._check(lib.sfb_enable_timing(self._ctx, 1 if on else 0), "sfb_enable_timing")
+
+    def kernel_time_ms(self, which):
+        ms, n = C.c_double(), C.c_int64()
+        self._check(lib.sfb_kernel_time_ms(self._ctx, int(which), C.byref(ms), C.byref(n)), "sfb_kernel_time_ms")
+        return ms.value, n.value
+
+    def reset_timing(self):
+        self._check(lib.sfb_reset_timing(self._ctx), "sfb_reset_timing")

@@ -1,0 +1,340 @@
+// C ABI of the SFB library (see include/sfb.h): argument validation, launch plans,
+// and the order of kernel launches for one bulk-synchronous SFB iteration.
+// Host code only; every step of the computation runs in the kernels.
+#include "../../include/sfb.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <new>
+#include <vector>
+
+#include "sfb_kernels.h"
+
+using namespace sfb;
+
+namespace {
+constexpr int kFamilies = 4;  // 0 scores, 1 factor u, 2 reconstruct-apply, 3 sparse helpers
+struct EventPair { hipEvent_t a, b; };
+}  // namespace
+
+struct sfb_ctx {
+    sfb_model model;
+    int64_t J, D;
+    int32_t P, B;
+    sfb_dtype dtype;
+    hipStream_t stream;
+    FwdPlan fwd_all, fwd_worker;   // scores of all N rows / of one worker's B rows
+    ReconPlan recon;
+    void* ws;
+    size_t ws_bytes;
+    int last_hip;
+    bool timing;
+    std::vector<EventPair> used[kFamilies], spare;
+};
+
+namespace {
+
+inline int64_t round_up4(int64_t x) { return (x + 3) / 4 * 4; }
+
+size_t workspace_need(const sfb_ctx* c) {
+    const int64_t ldz = round_up4(c->J);
+    const size_t all = (size_t)c->fwd_all.split_k * (size_t)c->P * c->B * ldz * sizeof(float);
+    const size_t one = (size_t)c->fwd_worker.split_k * (size_t)c->B * ldz * sizeof(float);
+    return all > one ? all : one;
+}
+
+sfb_status hip_fail(sfb_ctx* c, hipError_t e) {
+    c->last_hip = (int)e;
+    return SFB_EHIP;
+}
+
+// Brackets one launch with events when timing is on.
+struct Timed {
+    sfb_ctx* c;
+    int fam;
+    EventPair ev;
+    bool on;
+    Timed(sfb_ctx* ctx, int family) : c(ctx), fam(family), on(ctx->timing) {
+        if (!on) return;
+        if (!c->spare.empty()) {
+            ev = c->spare.back();
+            c->spare.pop_back();
+        } else if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) {
+            on = false;
+            return;
+        }
+        (void)hipEventRecord(ev.a, c->stream);
+    }
+    ~Timed() {
+        if (!on) return;
+        (void)hipEventRecord(ev.b, c->stream);
+        c->used[fam].push_back(ev);
+    }
+};
+
+sfb_status check_common(const sfb_ctx* c, const float* W, int64_t ldw, const float* U, int64_t ldu,
+                        const void* V, int64_t ldv) {
+    if (!c || !W || !U || !V) return SFB_EINVAL;
+    if (ldw < c->D || ldu < c->J || ldv < c->D) return SFB_ESHAPE;
+    return SFB_OK;
+}
+
+sfb_status check_batch(const sfb_ctx* c, const sfb_batch* b, const int32_t* y) {
+    if (!b || !y) return SFB_EINVAL;
+    if (c->model == SFB_L2SVM) {
+        if (!b->csr_rowptr || (b->nnz > 0 && (!b->csr_col || !b->csr_val))) return SFB_EINVAL;
+        if (b->nnz < 0) return SFB_ESHAPE;
+    } else {
+        if (!b->a) return SFB_EINVAL;
+        if (c->model == SFB_DML && !b->a2) return SFB_EINVAL;
+        if (b->lda < c->D) return SFB_ESHAPE;
+    }
+    return SFB_OK;
+}
+
+// Factors of `n_rows` samples whose outputs start at row `row0` of U, V, loss.
+sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t ldw, const sfb_batch* b,
+                        const int32_t* y, int64_t row0, int n_rows, float* U, int64_t ldu, void* V,
+                        int64_t ldv, float* loss) {
+    if (c->ws == nullptr || c->ws_bytes < workspace_need(c)) return SFB_EWORKSPACE;
+    const bool bf16 = c->dtype == SFB_BF16;
+    const size_t vsz = bf16 ? 2 : 4;
+    void* v_rows = (char*)V + (size_t)row0 * ldv * vsz;
+    const int64_t ldz = round_up4(c->J);
+
+    FwdArgs f{};
+    f.w = W; f.ldw = ldw;
+    f.zp = (float*)c->ws; f.ldz = ldz; f.zstride = (int64_t)n_rows * ldz;
+    f.n_rows = n_rows; f.J = (int)c->J; f.D = (int)c->D;
+    f.bf16 = bf16;
+    if (c->model == SFB_L2SVM) {
+        // v_i first: the dense rows then feed the score contraction as its A operand.
+        DensifyArgs d{b->csr_rowptr, b->csr_col, b->csr_val, (float*)v_rows, ldv, n_rows, (int)c->D, b->nnz};
+        {
+            Timed t(c, 3);
+            hipError_t e = launch_csr_densify(d, c->stream);
+            if (e != hipSuccess) return hip_fail(c, e);
+        }
+        f.a = v_rows; f.a2 = nullptr; f.lda = ldv; f.v = nullptr; f.ldv = 0; f.diff = false;
+    } else {
+        f.a = b->a; f.a2 = (c->model == SFB_DML) ? b->a2 : nullptr; f.lda = b->lda;
+        f.v = v_rows; f.ldv = ldv; f.diff = (c->model == SFB_DML);
+    }
+    {
+        Timed t(c, 0);
+        hipError_t e = launch_forward(f, plan, c->stream);
+        if (e != hipSuccess) return hip_fail(c, e);
+    }
+    FactorArgs g{};
+    g.zp = (const float*)c->ws; g.ldz = ldz; g.zstride = f.zstride; g.split_k = plan.split_k;
+    g.y = y; g.u = U + row0 * ldu; g.ldu = ldu; g.loss = loss ? loss + row0 : nullptr;
+    g.n_rows = n_rows; g.J = (int)c->J; g.model = (Model)c->model;
+    {
+        Timed t(c, 1);
+        hipError_t e = launch_factor(g, c->stream);
+        if (e != hipSuccess) return hip_fail(c, e);
+    }
+    return SFB_OK;
+}
+
+sfb_status check_recon(const sfb_ctx* c, float eta, float scale, const uint8_t* active) {
+    if (!std::isfinite(eta) || !std::isfinite(scale)) return SFB_EINVAL;
+    if (active && c->P > 64) return SFB_EUNSUPPORTED;
+    return SFB_OK;
+}
+
+sfb_status recon_launch(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64_t ldu, const void* V,
+                        int64_t ldv, float eta, float scale, const uint8_t* active) {
+    ReconArgs r{};
+    r.w = W; r.ldw = ldw; r.u = U; r.ldu = ldu; r.v = V; r.ldv = ldv;
+    r.J = (int)c->J; r.D = (int)c->D; r.N = c->P * c->B; r.B = c->B;
+    r.alpha = -eta * scale;
+    r.bf16 = c->dtype == SFB_BF16;
+    r.use_mask = false;
+    r.live_mask = ~0ull;
+    if (active) {
+        uint64_t m = 0;
+        bool all = true;
+        for (int p = 0; p < c->P; ++p) {
+            if (active[p]) m |= (1ull << p); else all = false;
+        }
+        r.live_mask = m;
+        r.use_mask = !all;
+    }
+    Timed t(c, 2);
+    hipError_t e = launch_reconstruct(r, c->recon, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e);
+    return SFB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+sfb_status sfb_create(sfb_ctx** out, sfb_model m, int64_t J, int64_t D, int32_t P, int32_t B,
+                      sfb_dtype input_dtype, void* hip_stream) {
+    if (!out) return SFB_EINVAL;
+    *out = nullptr;
+    if (J <= 0 || D <= 0 || P <= 0 || B <= 0) return SFB_EINVAL;
+    if (m != SFB_MLR && m != SFB_DML && m != SFB_L2SVM) return SFB_EINVAL;
+    if (input_dtype != SFB_F32 && input_dtype != SFB_BF16) return SFB_EDTYPE;
+    if (input_dtype == SFB_BF16 && m != SFB_MLR) return SFB_EUNSUPPORTED;
+    // kernels index rows and columns with 32-bit ints
+    if (J > (1 << 30) || D > (1 << 30) || (int64_t)P * B > (1 << 30)) return SFB_EUNSUPPORTED;
+    sfb_ctx* c = new (std::nothrow) sfb_ctx();
+    if (!c) return SFB_EINVAL;
+    c->model = m; c->J = J; c->D = D; c->P = P; c->B = B; c->dtype = input_dtype;
+    c->stream = (hipStream_t)hip_stream;
+    c->fwd_all = plan_forward((int64_t)P * B, J, D);
+    c->fwd_worker = plan_forward(B, J, D);
+    c->recon = plan_reconstruct(J, D, (int64_t)P * B);
+    c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->timing = false;
+    *out = c;
+    return SFB_OK;
+}
+
+void sfb_destroy(sfb_ctx* c) {
+    if (!c) return;
+    for (int f = 0; f < kFamilies; ++f)
+        for (auto& e : c->used[f]) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    for (auto& e : c->spare) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    delete c;
+}
+
+sfb_status sfb_workspace_bytes(const sfb_ctx* c, size_t* bytes) {
+    if (!c || !bytes) return SFB_EINVAL;
+    *bytes = workspace_need(c);
+    return SFB_OK;
+}
+
+sfb_status sfb_set_workspace(sfb_ctx* c, void* dev, size_t bytes) {
+    if (!c || !dev) return SFB_EINVAL;
+    if (((uintptr_t)dev % 16) != 0) return SFB_EINVAL;
+    if (bytes < workspace_need(c)) return SFB_EWORKSPACE;
+    c->ws = dev; c->ws_bytes = bytes;
+    return SFB_OK;
+}
+
+sfb_status sfb_compute_factors(sfb_ctx* c, const float* W, int64_t ldw, const sfb_batch* batch,
+                               const int32_t* y, float* U, int64_t ldu, void* V, int64_t ldv, float* loss) {
+    sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
+    if (s != SFB_OK) return s;
+    s = check_batch(c, batch, y);
+    if (s != SFB_OK) return s;
+    return factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss);
+}
+
+sfb_status sfb_compute_factors_worker(sfb_ctx* c, const float* W, int64_t ldw, const sfb_batch* batch_p,
+                                      const int32_t* y_p, int32_t p, float* U, int64_t ldu, void* V,
+                                      int64_t ldv, float* loss) {
+    sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
+    if (s != SFB_OK) return s;
+    s = check_batch(c, batch_p, y_p);
+    if (s != SFB_OK) return s;
+    if (p < 0 || p >= c->P) return SFB_ESHAPE;
+    return factors_rows(c, c->fwd_worker, W, ldw, batch_p, y_p, (int64_t)p * c->B, c->B, U, ldu, V, ldv, loss);
+}
+
+sfb_status sfb_reconstruct_apply(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64_t ldu,
+                                 const void* V, int64_t ldv, float eta, float scale, const uint8_t* active) {
+    sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
+    if (s != SFB_OK) return s;
+    s = check_recon(c, eta, scale, active);
+    if (s != SFB_OK) return s;
+    return recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active);
+}
+
+sfb_status sfb_step(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, const int32_t* y, float* U,
+                    int64_t ldu, void* V, int64_t ldv, float* loss, float eta, const uint8_t* active) {
+    sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
+    if (s != SFB_OK) return s;
+    s = check_batch(c, batch, y);
+    if (s != SFB_OK) return s;
+    const float scale = 1.0f / (float)c->B;   // mini-batch mean inside a worker (Section 3)
+    s = check_recon(c, eta, scale, active);
+    if (s != SFB_OK) return s;
+    s = factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss);
+    if (s != SFB_OK) return s;
+    return recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active);
+}
+
+sfb_status sfb_sync(sfb_ctx* c) {
+    if (!c) return SFB_EINVAL;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return hip_fail(c, e);
+    return SFB_OK;
+}
+
+const char* sfb_strerror(sfb_status s) {
+    switch (s) {
+        case SFB_OK: return "ok";
+        case SFB_EINVAL: return "invalid argument (null pointer, non-positive size, non-finite eta or scale)";
+        case SFB_ESHAPE: return "shape mismatch (leading dimension shorter than the row, negative nnz, worker index out of range)";
+        case SFB_EDTYPE: return "unknown dtype";
+        case SFB_EWORKSPACE: return "workspace missing or too small";
+        case SFB_EUNSUPPORTED: return "unsupported model/dtype combination or size";
+        case SFB_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int sfb_last_hip_error(const sfb_ctx* c) { return c ? c->last_hip : 0; }
+
+sfb_status sfb_plan_info(const sfb_ctx* c, int32_t* fwd_split_k, int32_t* fwd_grid, int32_t* recon_grid) {
+    if (!c) return SFB_EINVAL;
+    if (fwd_split_k) *fwd_split_k = c->fwd_all.split_k;
+    if (fwd_grid) *fwd_grid = c->fwd_all.grid;
+    if (recon_grid) *recon_grid = c->recon.grid;
+    return SFB_OK;
+}
+
+sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k, int32_t recon_variant) {
+    if (!c) return SFB_EINVAL;
+    if ((fwd_bm > 0 && fwd_bm != 64 && fwd_bm != 128) || (fwd_bn > 0 && fwd_bn != 64 && fwd_bn != 128))
+        return SFB_EINVAL;
+    if (recon_variant > 3 || fwd_split_k > 64) return SFB_EINVAL;
+    FwdPlan p = c->fwd_all;
+    if (fwd_bm > 0) p.bm = fwd_bm;
+    if (fwd_bn > 0) p.bn = fwd_bn;
+    if (fwd_split_k > 0) p.split_k = fwd_split_k;
+    finish_forward_plan(&p, (int64_t)c->P * c->B, c->J, c->D);
+    c->fwd_all = p;
+    if (recon_variant >= 0) c->recon = plan_reconstruct_variant(c->J, c->D, recon_variant);
+    return SFB_OK;
+}
+
+sfb_status sfb_enable_timing(sfb_ctx* c, int enable) {
+    if (!c) return SFB_EINVAL;
+    c->timing = enable != 0;
+    return SFB_OK;
+}
+
+sfb_status sfb_kernel_time_ms(sfb_ctx* c, int which, double* ms, int64_t* launches) {
+    if (!c || which < 0 || which >= kFamilies || !ms) return SFB_EINVAL;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return hip_fail(c, e);
+    double total = 0.0;
+    for (auto& p : c->used[which]) {
+        float t = 0.f;
+        e = hipEventElapsedTime(&t, p.a, p.b);
+        if (e != hipSuccess) return hip_fail(c, e);
+        total += t;
+    }
+    *ms = total;
+    if (launches) *launches = (int64_t)c->used[which].size();
+    return SFB_OK;
+}
+
+sfb_status sfb_reset_timing(sfb_ctx* c) {
+    if (!c) return SFB_EINVAL;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return hip_fail(c, e);
+    for (int f = 0; f < kFamilies; ++f) {
+        for (auto& p : c->used[f]) c->spare.push_back(p);
+        c->used[f].clear();
+    }
+    return SFB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Device-side helpers shared by the SFB kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sfb {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint16_t bf16_t;  // storage only: the upper 16 bits of an IEEE fp32
+
+constexpr int kWave = 64;
+constexpr int kXcds = 8;  // MI355X: 8 accelerator dies, each with its own L2
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round to nearest, ties to even.  NaN stays NaN (quiet bit forced).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// Four consecutive elements of one row starting at column `col`, widened to fp32.
+// Elements at or beyond `ncols` read as 0.  `vec` promises that `row + col` is
+// suitably aligned for a single wide load (checked on the host).
+__device__ __forceinline__ f32x4 load4(const float* __restrict__ row, int64_t col, int64_t ncols, bool vec) {
+    f32x4 r = {0.f, 0.f, 0.f, 0.f};
+    if (vec && col + 3 < ncols) {
+        r = *reinterpret_cast<const f32x4*>(row + col);
+    } else {
+        if (col + 0 < ncols) r.x = row[col + 0];
+        if (col + 1 < ncols) r.y = row[col + 1];
+        if (col + 2 < ncols) r.z = row[col + 2];
+        if (col + 3 < ncols) r.w = row[col + 3];
+    }
+    return r;
+}
+
+__device__ __forceinline__ f32x4 load4(const bf16_t* __restrict__ row, int64_t col, int64_t ncols, bool vec) {
+    f32x4 r = {0.f, 0.f, 0.f, 0.f};
+    if (vec && col + 3 < ncols) {
+        uint2 p = *reinterpret_cast<const uint2*>(row + col);
+        r.x = __uint_as_float(p.x << 16);
+        r.y = __uint_as_float(p.x & 0xffff0000u);
+        r.z = __uint_as_float(p.y << 16);
+        r.w = __uint_as_float(p.y & 0xffff0000u);
+    } else {
+        if (col + 0 < ncols) r.x = bf16_to_f32(row[col + 0]);
+        if (col + 1 < ncols) r.y = bf16_to_f32(row[col + 1]);
+        if (col + 2 < ncols) r.z = bf16_to_f32(row[col + 2]);
+        if (col + 3 < ncols) r.w = bf16_to_f32(row[col + 3]);
+    }
+    return r;
+}
+
+__device__ __forceinline__ void store4(float* __restrict__ row, int64_t col, int64_t ncols, bool vec, f32x4 v) {
+    if (vec && col + 3 < ncols) {
+        *reinterpret_cast<f32x4*>(row + col) = v;
+    } else {
+        if (col + 0 < ncols) row[col + 0] = v.x;
+        if (col + 1 < ncols) row[col + 1] = v.y;
+        if (col + 2 < ncols) row[col + 2] = v.z;
+        if (col + 3 < ncols) row[col + 3] = v.w;
+    }
+}
+
+__device__ __forceinline__ void store4(bf16_t* __restrict__ row, int64_t col, int64_t ncols, bool vec, f32x4 v) {
+    if (vec && col + 3 < ncols) {
+        uint2 p;
+        p.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+        p.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+        *reinterpret_cast<uint2*>(row + col) = p;
+    } else {
+        if (col + 0 < ncols) row[col + 0] = f32_to_bf16(v.x);
+        if (col + 1 < ncols) row[col + 1] = f32_to_bf16(v.y);
+        if (col + 2 < ncols) row[col + 2] = f32_to_bf16(v.z);
+        if (col + 3 < ncols) row[col + 3] = f32_to_bf16(v.w);
+    }
+}
+
+// Workgroups are handed to the 8 dies round-robin by linear id.  Renumber so that each
+// die owns one contiguous range of tile ids (tiles that share operands then share an L2).
+__device__ __forceinline__ int xcd_contiguous_id(int linear_id, int total) {
+    const int xcd = linear_id % kXcds;
+    const int slot = linear_id / kXcds;
+    const int q = total / kXcds, r = total % kXcds;
+    return xcd * q + (xcd < r ? xcd : r) + slot;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+}  // namespace sfb

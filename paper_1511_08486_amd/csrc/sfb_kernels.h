@@ -1,0 +1,81 @@
+// Host-callable launchers of the SFB kernels.  Internal to the library: the public
+// surface is include/sfb.h.  Every launcher validates nothing; the C ABI layer has
+// already checked shapes and pointers.  Each returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sfb {
+
+enum Model { kMLR = 0, kDML = 1, kL2SVM = 2 };
+
+struct FwdPlan {
+    int bm, bn;      // output tile: samples x classes
+    int split_k;     // slices of the D-long contraction
+    int k_slice;     // columns of D per slice (multiple of the K chunk)
+    int grid;        // workgroups
+};
+
+// Chooses tile and split for Z[n_rows][J] = A W^T with contraction length D.
+FwdPlan plan_forward(int64_t n_rows, int64_t J, int64_t D);
+// Recomputes k_slice / grid after bm, bn or split_k were set by hand (split_k is clamped
+// so that no slice is empty).
+void finish_forward_plan(FwdPlan* p, int64_t n_rows, int64_t J, int64_t D);
+
+struct FwdArgs {
+    const void* a;        // [n_rows][lda] features (fp32 or bf16)
+    const void* a2;       // second point of the pair (DML) or nullptr
+    int64_t lda;
+    const float* w;       // [J][ldw]
+    int64_t ldw;
+    float* zp;            // [split_k][n_rows][ldz] partial scores
+    int64_t ldz, zstride;
+    void* v;              // [n_rows][ldv] out: a (or a - a2); nullptr = do not write
+    int64_t ldv;
+    int n_rows, J, D;
+    bool bf16, diff;
+};
+hipError_t launch_forward(const FwdArgs& a, const FwdPlan& p, hipStream_t s);
+
+struct FactorArgs {
+    const float* zp;      // [split_k][n_rows][ldz]
+    int64_t ldz, zstride;
+    int split_k;
+    const int32_t* y;     // [n_rows]
+    float* u;             // [n_rows][ldu]
+    int64_t ldu;
+    float* loss;          // [n_rows] or nullptr
+    int n_rows, J;
+    Model model;
+};
+hipError_t launch_factor(const FactorArgs& a, hipStream_t s);
+
+struct DensifyArgs {
+    const int32_t* rowptr; const int32_t* col; const float* val;
+    float* v; int64_t ldv;
+    int n_rows, D;
+    int64_t nnz;          // length of col / val
+};
+hipError_t launch_csr_densify(const DensifyArgs& a, hipStream_t s);
+
+struct ReconPlan {
+    int variant;          // index into the tile table
+    int bm, bn;           // W tile: rows (J) x columns (D)
+    int grid;
+};
+ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N);
+ReconPlan plan_reconstruct_variant(int64_t J, int64_t D, int variant);
+
+struct ReconArgs {
+    float* w; int64_t ldw;         // [J][ldw] read-modify-write
+    const float* u; int64_t ldu;   // [N][ldu]
+    const void* v; int64_t ldv;    // [N][ldv] fp32 or bf16
+    int J, D, N;
+    int B;                         // samples per worker (rows of one mask bit)
+    float alpha;                   // -eta * scale
+    uint64_t live_mask;            // bit p = worker p contributes
+    bool use_mask, bf16;
+};
+hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s);
+
+}  // namespace sfb

@@ -1,0 +1,191 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the
+same seeded inputs.  fp32 configs: max relative error 1e-4 (with a floor of 1e-2 of the
+largest magnitude); bf16-input config: 2e-2."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_util import alloc_factors, assert_close, run_chain, to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL32 = 1e-4
+TOLBF = 2e-2
+
+
+@pytest.fixture(scope="module")
+def sfb():
+    import paper_1511_08486_amd as m
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return m
+
+
+def test_mlr_tiny_five_steps(sfb):
+    wl = workloads.make("mlr_tiny")
+    worst = run_chain(wl, wl.steps, TOL32)
+    print("mlr_tiny worst error/allowance", worst)
+
+
+@pytest.mark.parametrize("J,D,P,B", [(1, 1, 1, 1), (3, 2, 1, 1), (37, 203, 3, 5), (130, 131, 2, 33),
+                                     (333, 1111, 5, 77), (64, 128, 2, 16), (257, 516, 4, 40)])
+def test_mlr_ragged_shapes(sfb, J, D, P, B):
+    wl = workloads.make("mlr_tiny", seed=J + D, J=J, D=D, P=P, B=B, steps=3)
+    run_chain(wl, 3, TOL32)
+
+
+@pytest.mark.parametrize("pad", [1, 4])
+def test_padded_leading_dimensions(sfb, pad):
+    """ld > row length; pad=1 also breaks 16-byte row alignment (scalar paths)."""
+    wl = workloads.make("mlr_tiny", seed=5, J=70, D=300, P=3, B=20, steps=2)
+    run_chain(wl, 2, TOL32, pad=pad)
+
+
+def test_mlr_medium_hundred_steps(sfb):
+    wl = workloads.make("mlr_medium")
+    worst = run_chain(wl, wl.steps, TOL32, check_every=7)
+    print("mlr_medium worst error/allowance", worst)
+
+
+@pytest.mark.parametrize("plan", [dict(fwd_bm=64, fwd_bn=64, fwd_split_k=3, recon_variant=0),
+                                  dict(fwd_bm=128, fwd_bn=64, fwd_split_k=1, recon_variant=2),
+                                  dict(fwd_bm=64, fwd_bn=128, fwd_split_k=16, recon_variant=3),
+                                  dict(fwd_bm=128, fwd_bn=128, fwd_split_k=5, recon_variant=1)])
+def test_every_tile_variant(sfb, plan):
+    wl = workloads.make("mlr_medium", J=520, D=1000, P=4, B=50, steps=2, pool=2)
+    run_chain(wl, 2, TOL32, plan=plan)
+
+
+def test_dml_twenty_steps(sfb):
+    wl = workloads.make("dml", seed=1)    # seed 1 keeps every pair > 1e-4 from the hinge kink
+    worst = run_chain(wl, wl.steps, TOL32, check_every=3)
+    print("dml worst error/allowance", worst)
+
+
+def test_dml_ragged(sfb):
+    wl = workloads.make("dml", seed=2, J=45, D=333, P=3, B=21, steps=3)
+    run_chain(wl, 3, TOL32, dml_guard=1e-5)
+
+
+def test_l2svm_twenty_steps(sfb):
+    wl = workloads.make("l2svm")
+    worst = run_chain(wl, wl.steps, TOL32, check_every=4)
+    print("l2svm worst error/allowance", worst)
+
+
+def test_l2svm_ragged_and_empty_rows(sfb):
+    wl = workloads.make("l2svm", seed=3, J=77, D=501, P=3, B=11, steps=2, density=0.05)
+    # make two rows empty and one row a single entry
+    for b in wl.batches:
+        per = b["rowptr"][1]
+        counts = np.full(wl.N, per)
+        counts[[0, 7]] = 0
+        counts[3] = 1
+        keep = np.concatenate([np.arange(r * per, r * per + counts[r]) for r in range(wl.N)]).astype(np.int64)
+        b["col"], b["val"] = b["col"][keep], b["val"][keep]
+        b["rowptr"] = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    run_chain(wl, 2, TOL32)
+
+
+def test_mlr_large_bf16_two_steps(sfb):
+    wl = workloads.make("mlr_large", pool=2)
+    worst = run_chain(wl, 2, TOLBF)
+    print("mlr_large worst error/allowance", worst)
+
+
+def test_bf16_ragged(sfb):
+    wl = workloads.make("mlr_large", seed=4, J=300, D=1004, P=3, B=30, steps=2, pool=2)
+    run_chain(wl, 2, TOLBF)
+
+
+def test_worker_calls_equal_batched_call_and_mask_drops_a_worker(sfb):
+    wl = workloads.make("mlr_medium", J=200, D=520, P=4, B=24, steps=1, pool=1)
+    dev = "cuda:0"
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+    b = wl.batch(0)
+    db, dy = to_device(wl, b, dev)
+    W = torch.from_numpy(wl.W0).to(dev)
+    U, V, loss = alloc_factors(wl, dev)
+    ctx.compute_factors(W, db, dy, U, V, loss)
+    U2, V2, loss2 = alloc_factors(wl, dev)
+    for p in reversed(range(wl.P)):          # any commit order gives the same buffers
+        rows = slice(p * wl.B, (p + 1) * wl.B)
+        ctx.compute_factors_worker(W, sfb.SfbBatch(a=db.a[rows]), dy[rows], p, U2, V2, loss2)
+    ctx.sync()
+    Uo, Vo, fo = oracle.factors(wl.model, wl.W0, b)
+    for got in (U, U2):
+        assert_close(got.cpu().numpy(), Uo, TOL32, "U")
+    assert torch.equal(V, V2) and np.array_equal(V.cpu().numpy(), b["A"])      # v = a, bit for bit
+    assert_close(loss2.cpu().numpy(), fo, TOL32, "loss")
+    # MLR invariant on the device buffer: residual rows sum to zero
+    assert float(U.sum(dim=1).abs().max()) < 1e-5
+    # reconstruction with worker 2 dead, plain-sum scale
+    active = [1, 1, 0, 1]
+    W1 = W.clone()
+    ctx.reconstruct_apply(W1, U, V, eta=0.3, scale=1.0, active=active)
+    ctx.sync()
+    want = oracle.apply_update(wl.W0, oracle.delta_w(Uo, Vo, wl.P, wl.B, active) * wl.B, 0.3)
+    assert_close(W1.cpu().numpy(), want, TOL32, "W with dead worker")
+    # a dead worker's buffers may hold anything, even NaN
+    U3, V3 = U.clone(), V.clone()
+    U3[2 * wl.B:3 * wl.B] = float("nan")
+    V3[2 * wl.B:3 * wl.B] = float("inf")
+    W2 = W.clone()
+    ctx.reconstruct_apply(W2, U3, V3, eta=0.3, scale=1.0, active=active)
+    ctx.sync()
+    assert torch.equal(W1, W2)
+    ctx.close()
+
+
+def test_zero_factors_leave_w_bit_identical_and_eta_zero_is_identity(sfb):
+    wl = workloads.make("dml", seed=1, J=96, D=260, P=2, B=40, steps=1, pool=1)
+    dev = "cuda:0"
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+    db, dy = to_device(wl, wl.batch(0), dev)
+    U, V, loss = alloc_factors(wl, dev)
+    W = torch.zeros((wl.J, wl.D), device=dev)            # z = 0 -> u = 0 -> W stays 0
+    ctx.step(W, db, dy, U, V, 0.5, loss=loss)
+    ctx.sync()
+    assert not U.any() and not W.any()
+    assert np.array_equal(loss.cpu().numpy(), np.where(wl.batch(0)["y"] == 1, 0.0, 1.0).astype(np.float32))
+    W = torch.from_numpy(wl.W0).to(dev)
+    ctx.step(W, db, dy, U, V, 0.0)
+    ctx.sync()
+    assert torch.equal(W.cpu(), torch.from_numpy(wl.W0))
+    ctx.close()
+
+
+def test_results_do_not_depend_on_the_launch_plan_beyond_rounding(sfb):
+    """Same inputs, two different tilings: W agrees to fp32 rounding (replicas that tile
+    differently would drift only at this level)."""
+    wl = workloads.make("mlr_medium", J=300, D=700, P=4, B=32, steps=1, pool=1)
+    outs = []
+    for plan in (dict(fwd_split_k=1, recon_variant=0), dict(fwd_split_k=4, recon_variant=2)):
+        dev = "cuda:0"
+        ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+        ctx.set_plan(**plan)
+        db, dy = to_device(wl, wl.batch(0), dev)
+        W = torch.from_numpy(wl.W0).to(dev)
+        U, V, _ = alloc_factors(wl, dev)
+        ctx.step(W, db, dy, U, V, wl.eta)
+        ctx.sync()
+        outs.append(W.cpu().numpy())
+        ctx.close()
+    assert_close(outs[0], outs[1], 1e-6, "W across plans")
+
+
+def test_determinism_same_call_twice_is_bit_identical(sfb):
+    wl = workloads.make("mlr_medium", J=500, D=2048, P=8, B=32, steps=1, pool=1)
+    dev = "cuda:0"
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+    db, dy = to_device(wl, wl.batch(0), dev)
+    res = []
+    for _ in range(2):
+        W = torch.from_numpy(wl.W0).to(dev)
+        U, V, _ = alloc_factors(wl, dev)
+        ctx.step(W, db, dy, U, V, wl.eta)
+        ctx.sync()
+        res.append((W.clone(), U.clone()))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+    ctx.close()

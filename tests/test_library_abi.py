@@ -1,0 +1,110 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header
+declares, and its host-side validation rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_1511_08486_amd as sfb
+    return sfb.lib
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sfb.h")).read()
+    return sorted(set(re.findall(r"SFB_API[^;(]*?\b(sfb_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_symbols()
+    for must in ("sfb_create", "sfb_destroy", "sfb_compute_factors", "sfb_compute_factors_worker",
+                 "sfb_reconstruct_apply", "sfb_step", "sfb_sync", "sfb_strerror", "sfb_workspace_bytes",
+                 "sfb_set_workspace"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    raw = C.CDLL(os.path.join(ROOT, "paper_1511_08486_amd", "libsfb.so"))
+    for name in declared_symbols():
+        assert hasattr(raw, name), f"libsfb.so lacks {name}"
+
+
+def test_create_validates_arguments(lib):
+    import paper_1511_08486_amd as sfb
+    ctx = C.c_void_p()
+    assert lib.sfb_create(None, 0, 10, 10, 1, 1, 0, None) == -1
+    assert lib.sfb_create(C.byref(ctx), 0, 0, 10, 1, 1, 0, None) == -1
+    assert lib.sfb_create(C.byref(ctx), 0, 10, 10, 0, 1, 0, None) == -1
+    assert lib.sfb_create(C.byref(ctx), 7, 10, 10, 1, 1, 0, None) == -1
+    assert lib.sfb_create(C.byref(ctx), 0, 10, 10, 1, 1, 5, None) == -3
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_DML, 10, 10, 1, 1, sfb.SFB_BF16, None) == -6
+    assert not ctx.value
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 1000, 4096, 8, 64, sfb.SFB_F32, None) == 0
+    need = C.c_size_t()
+    assert lib.sfb_workspace_bytes(ctx, C.byref(need)) == 0
+    k, g, r = C.c_int32(), C.c_int32(), C.c_int32()
+    assert lib.sfb_plan_info(ctx, C.byref(k), C.byref(g), C.byref(r)) == 0
+    assert need.value == k.value * 512 * 1000 * 4 and g.value >= 256 and r.value >= 256
+    lib.sfb_destroy(ctx)
+
+
+def test_calls_reject_bad_arguments_before_launching(lib):
+    """Fake non-null pointers are safe here: validation fails first, nothing is launched."""
+    import paper_1511_08486_amd as sfb
+    ctx = C.c_void_p()
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 8, 16, 2, 4, sfb.SFB_F32, None) == 0
+    fake = C.c_void_p(0x1000)
+    b = sfb.binding.sfb_batch()
+    b.a, b.lda = 0x1000, 16
+    # null W / U / V
+    assert lib.sfb_compute_factors(ctx, None, 16, C.byref(b), fake, fake, 8, fake, 16, None) == -1
+    assert lib.sfb_reconstruct_apply(ctx, fake, 16, None, 8, fake, 16, 0.1, 1.0, None) == -1
+    # leading dimensions shorter than the rows
+    assert lib.sfb_compute_factors(ctx, fake, 15, C.byref(b), fake, fake, 8, fake, 16, None) == -2
+    assert lib.sfb_compute_factors(ctx, fake, 16, C.byref(b), fake, fake, 7, fake, 16, None) == -2
+    assert lib.sfb_reconstruct_apply(ctx, fake, 16, fake, 8, fake, 15, 0.1, 1.0, None) == -2
+    b.lda = 15
+    assert lib.sfb_compute_factors(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None) == -2
+    b.lda = 16
+    # missing batch / labels / features
+    assert lib.sfb_compute_factors(ctx, fake, 16, None, fake, fake, 8, fake, 16, None) == -1
+    assert lib.sfb_compute_factors(ctx, fake, 16, C.byref(b), None, fake, 8, fake, 16, None) == -1
+    b.a = None
+    assert lib.sfb_compute_factors(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None) == -1
+    b.a = 0x1000
+    # worker index out of range
+    assert lib.sfb_compute_factors_worker(ctx, fake, 16, C.byref(b), fake, 2, fake, 8, fake, 16, None) == -2
+    # no workspace registered yet
+    assert lib.sfb_compute_factors(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None) == -5
+    assert lib.sfb_set_workspace(ctx, fake, 1) == -5
+    assert lib.sfb_set_workspace(ctx, C.c_void_p(0x1004), 1 << 20) == -1      # not 16-byte aligned
+    # non-finite learning rate
+    assert lib.sfb_reconstruct_apply(ctx, fake, 16, fake, 8, fake, 16, float("nan"), 1.0, None) == -1
+    assert lib.sfb_step(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None, float("inf"), None) == -1
+    # plan override outside the table
+    assert lib.sfb_set_plan(ctx, 96, 0, 0, -1) == -1 and lib.sfb_set_plan(ctx, 0, 0, 0, 9) == -1
+    lib.sfb_destroy(ctx)
+    # a mask needs P <= 64
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 8, 16, 65, 1, sfb.SFB_F32, None) == 0
+    mask = (C.c_uint8 * 65)(*([1] * 65))
+    assert lib.sfb_reconstruct_apply(ctx, fake, 16, fake, 8, fake, 16, 0.1, 1.0, C.cast(mask, C.c_void_p)) == -6
+    lib.sfb_destroy(ctx)
+    # DML needs both points; L2SVM needs the CSR arrays
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_DML, 8, 16, 2, 4, sfb.SFB_F32, None) == 0
+    assert lib.sfb_compute_factors(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None) == -1
+    lib.sfb_destroy(ctx)
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_L2SVM, 8, 16, 2, 4, sfb.SFB_F32, None) == 0
+    assert lib.sfb_compute_factors(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None) == -1
+    lib.sfb_destroy(ctx)
+
+
+def test_strerror_covers_every_status(lib):
+    import paper_1511_08486_amd as sfb
+    seen = {sfb.sfb_strerror(s) for s in (0, -1, -2, -3, -5, -6, -7)}
+    assert len(seen) == 7 and "unknown status" not in seen
+    assert sfb.sfb_strerror(-99) == "unknown status"
