@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Throughput of the SFB hot path on one MI355X.
+
+A "step" is one full bulk-synchronous SFB iteration (scores, factor u, factor v, the
+concatenation standing in for the broadcast, reconstruction, W update) over one synthetic
+minibatch of P*B samples whose features, labels and W already sit in HBM.
+
+Prints ONE JSON line: whole-job samples/s (= P*B * steps/s), plus
+  roofline      the dominant kernel's achieved rate against the MI355X peak that bounds it,
+                from HIP events recorded around every launch of a second, instrumented pass
+  cpu_baseline  the fp64 numpy oracle timed on this host's cores on the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix-core peak
+PEAK_HBM_GBS = 8000.0
+FAMILIES = {0: "scores (fwd_scores_kernel)", 1: "factor u (factor_u_kernel)",
+            2: "reconstruct-apply (reconstruct_apply_kernel)", 3: "csr densify"}
+
+
+def cpu_baseline(wl, budget_s):
+    """The oracle as it stands, on the host cores, for a bounded number of steps."""
+    import numpy as np
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    W = wl.W0.astype(np.float64)
+    _, _, W, _ = oracle.step(wl.model, W, wl.batch(0), wl.P, wl.B, wl.eta)      # warm-up
+    n, t0 = 0, time.perf_counter()
+    while True:
+        _, _, W, _ = oracle.step(wl.model, W, wl.batch(n + 1), wl.P, wl.B, wl.eta)
+        n += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or n >= 200:
+            break
+    return {"value": wl.N * n / el, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n} consecutive fp64 numpy oracle steps of {wl.name} (after 1 warm-up step), "
+                      f"{el:.2f} s wall, {len(os.sched_getaffinity(0))} cores in the affinity mask",
+            "steps_per_s": n / el}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--config", default="mlr_medium")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="oracle timing budget (0 = skip)")
+    ap.add_argument("--plan", default="", help="fwd_bm,fwd_bn,split_k,recon_variant override")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1511_08486_amd as sfb
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    dev = "cuda:0"
+    wl = workloads.make(args.config)
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
+    if args.plan:
+        bm, bn, sk, rv = [int(x) for x in args.plan.split(",")]
+        ctx.set_plan(bm, bn, sk, rv)
+
+    # inputs resident in HBM before anything is timed
+    vdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    pool = []
+    for b in wl.batches:
+        y = torch.from_numpy(np.ascontiguousarray(b["y"], dtype=np.int32)).to(dev)
+        if wl.model == "mlr":
+            pool.append((sfb.SfbBatch(a=torch.from_numpy(b["A"]).to(vdt).to(dev)), y))
+        elif wl.model == "dml":
+            pool.append((sfb.SfbBatch(a=torch.from_numpy(b["X"]).to(dev), a2=torch.from_numpy(b["Y"]).to(dev)), y))
+        else:
+            pool.append((sfb.SfbBatch(rowptr=torch.from_numpy(b["rowptr"]).to(dev),
+                                      col=torch.from_numpy(b["col"]).to(dev),
+                                      val=torch.from_numpy(b["val"]).to(dev)), y))
+    W0 = torch.from_numpy(wl.W0).to(dev)
+    W = W0.clone()
+    U = torch.empty((wl.N, wl.J), dtype=torch.float32, device=dev)
+    V = torch.empty((wl.N, wl.D), dtype=vdt, device=dev)
+
+    def run(k):
+        for t in range(k):
+            b, y = pool[t % len(pool)]
+            ctx.step(W, b, y, U, V, wl.eta)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    W.copy_(W0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert bool(torch.isfinite(W).all()), "W is not finite after the timed steps"
+
+    # instrumented pass: same launches, HIP events around each one on the library's stream
+    W.copy_(W0)
+    ctx.enable_timing(True)
+    ctx.reset_timing()
+    k2 = min(args.steps, 500)
+    run(k2)
+    per_kernel = {}
+    for fam, name in FAMILIES.items():
+        ms, n = ctx.kernel_time_ms(fam)
+        if n:
+            per_kernel[fam] = (name, ms / n * 1e3, n)       # microseconds per launch
+    ctx.enable_timing(False)
+    ctx.reset_timing()
+
+    flops = 2.0 * wl.N * wl.J * wl.D                        # per launch, scores and reconstruction alike
+    dom = max((f for f in per_kernel if f in (0, 2)), key=lambda f: per_kernel[f][1])
+    us = per_kernel[dom][1]
+    achieved = flops / (us * 1e-6) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"{args.config}:{dom}")
+    roofline = {"bound": "mfma", "kernel": per_kernel[dom][0], "achieved": achieved,
+                "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                "traffic": traffic, "us_per_launch": us,
+                "kernels_us": {v[0]: round(v[1], 2) for v in per_kernel.values()}}
+
+    out = {
+        "metric": "sfb_samples_per_sec", "value": wl.N * args.steps / elapsed, "unit": "samples/s",
+        "steps_per_sec": args.steps / elapsed,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if wl.dtype == "f32" else "bf16 features, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.model} J={wl.J} D={wl.D} P={wl.P} B={wl.B} eta={wl.eta}",
+                   "plan": ctx.plan_info()},
+        "roofline": roofline,
+    }
+    if args.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -42,6 +42,7 @@ def test_padded_leading_dimensions(sfb, pad):
     run_chain(wl, 2, TOL32, pad=pad)
 
 
+@pytest.mark.timeout(600)
 def test_mlr_medium_hundred_steps(sfb):
     wl = workloads.make("mlr_medium")
     worst = run_chain(wl, wl.steps, TOL32, check_every=7)
@@ -68,6 +69,7 @@ def test_dml_ragged(sfb):
     run_chain(wl, 3, TOL32, dml_guard=1e-5)
 
 
+@pytest.mark.timeout(600)
 def test_l2svm_twenty_steps(sfb):
     wl = workloads.make("l2svm")
     worst = run_chain(wl, wl.steps, TOL32, check_every=4)
@@ -88,6 +90,7 @@ def test_l2svm_ragged_and_empty_rows(sfb):
     run_chain(wl, 2, TOL32)
 
 
+@pytest.mark.timeout(900)
 def test_mlr_large_bf16_two_steps(sfb):
     wl = workloads.make("mlr_large", pool=2)
     worst = run_chain(wl, 2, TOLBF)
