@@ -55,6 +55,44 @@ __device__ __forceinline__ f32x4 load4(const bf16_t* __restrict__ row, int64_t c
     return r;
 }
 
+// Unguarded, aligned 4-element loads for the fast paths (the caller clamps the address
+// into the matrix and discards what it must not use: no branches around memory ops).
+__device__ __forceinline__ f32x4 ldg4(const float* __restrict__ p) { return *reinterpret_cast<const f32x4*>(p); }
+__device__ __forceinline__ f32x4 ldg4(const bf16_t* __restrict__ p) {
+    const uint2 q = *reinterpret_cast<const uint2*>(p);
+    f32x4 r;
+    r.x = __uint_as_float(q.x << 16);
+    r.y = __uint_as_float(q.x & 0xffff0000u);
+    r.z = __uint_as_float(q.y << 16);
+    r.w = __uint_as_float(q.y & 0xffff0000u);
+    return r;
+}
+
+// Raw (unconverted) 4-element loads: what a prefetch keeps in registers until it is staged.
+template <typename T> struct RawOf;
+template <> struct RawOf<float> { typedef f32x4 type; };
+template <> struct RawOf<bf16_t> { typedef uint2 type; };
+__device__ __forceinline__ f32x4 ldraw4(const float* __restrict__ p) { return *reinterpret_cast<const f32x4*>(p); }
+__device__ __forceinline__ uint2 ldraw4(const bf16_t* __restrict__ p) { return *reinterpret_cast<const uint2*>(p); }
+__device__ __forceinline__ f32x4 widen4(f32x4 v) { return v; }
+__device__ __forceinline__ f32x4 widen4(uint2 q) {
+    f32x4 r;
+    r.x = __uint_as_float(q.x << 16);
+    r.y = __uint_as_float(q.x & 0xffff0000u);
+    r.z = __uint_as_float(q.y << 16);
+    r.w = __uint_as_float(q.y & 0xffff0000u);
+    return r;
+}
+// fp32 values that are exact bf16 (they were widened from bf16) back to their raw form
+template <typename T> __device__ __forceinline__ typename RawOf<T>::type to_raw(f32x4 v);
+template <> __device__ __forceinline__ f32x4 to_raw<float>(f32x4 v) { return v; }
+template <> __device__ __forceinline__ uint2 to_raw<bf16_t>(f32x4 v) {
+    uint2 q;
+    q.x = (__float_as_uint(v.x) >> 16) | (__float_as_uint(v.y) & 0xffff0000u);
+    q.y = (__float_as_uint(v.z) >> 16) | (__float_as_uint(v.w) & 0xffff0000u);
+    return q;
+}
+
 __device__ __forceinline__ void store4(float* __restrict__ row, int64_t col, int64_t ncols, bool vec, f32x4 v) {
     if (vec && col + 3 < ncols) {
         *reinterpret_cast<f32x4*>(row + col) = v;

@@ -23,7 +23,13 @@ constexpr int kFwdBK = 32;                 // columns of D per LDS stage
 constexpr int kFwdLds = kFwdBK + 4;        // padded row: conflict-free 128-bit reads
 constexpr int kFwdThreads = 256;
 
-template <int BM, int BN, typename TIn, bool DIFF>
+// Pipeline (one or two wavefronts per SIMD, so latency is hidden in the instruction
+// stream): features and W rows are fetched two stages ahead into registers as raw words,
+// converted / subtracted on the way into a double-buffered LDS tile (one barrier per
+// stage), and the operand fragments of the next 8 columns are read from LDS while the
+// MFMAs of the current 8 execute.  FAST: aligned pointers, D a multiple of 4 -- no branch
+// around any load (rows and columns are clamped into the matrix and zeroed by a select).
+template <int BM, int BN, typename TIn, bool DIFF, bool FAST>
 __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
     const TIn* __restrict__ A, const TIn* __restrict__ A2, int64_t lda, const float* __restrict__ W,
     int64_t ldw, float* __restrict__ Zp, int64_t ldz, int64_t zstride, TIn* __restrict__ V, int64_t ldv,
@@ -34,10 +40,13 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
     constexpr int MT = WM / 32, NT = WN / 32;
     constexpr int A_LD = BM * BK / 4 / kFwdThreads;  // 128-bit loads per thread per stage
     constexpr int B_LD = BN * BK / 4 / kFwdThreads;
+    constexpr int NQ = BK / 8;                       // fragment groups per stage
     static_assert(MT >= 1 && NT >= 1 && A_LD >= 1 && B_LD >= 1, "tile too small");
 
-    __shared__ float As[BM * LS];
-    __shared__ float Bs[BN * LS];
+    // two stages of the feature tile [BM][LS], then two stages of the W tile [BN][LS]
+    extern __shared__ __attribute__((aligned(16))) float fwd_lds[];
+    float* const As = fwd_lds;
+    float* const Bs = fwd_lds + 2 * BM * LS;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -55,45 +64,63 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
     const int n_chunks = (k_end - k_begin + BK - 1) / BK;
     const bool write_v = (V != nullptr) && (jb == 0);
 
-    f32x4 ra[A_LD], rb[B_LD];
+    using RawA = typename RawOf<TIn>::type;
+    struct Stage { RawA a[A_LD]; RawA a2[DIFF ? A_LD : 1]; f32x4 b[B_LD]; };
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-    auto fetch = [&](int k0) {
+    // Raw words only: nothing may depend on a load before the stage that consumes it.
+    auto fetch = [&](Stage& r, int k0) {
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
             const int idx = tid + i * kFwdThreads;
-            const int r = idx / (BK / 4), c = (idx % (BK / 4)) * 4;
-            const int row = n0 + r;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (row < n_rows) {
+            const int row = n0 + idx / (BK / 4), col = k0 + (idx % (BK / 4)) * 4;
+            if (FAST) {
+                const int64_t off = (int64_t)min(row, n_rows - 1) * lda + min(col, D - 4);
+                r.a[i] = ldraw4(A + off);
+                if (DIFF) r.a2[i] = ldraw4(A2 + off);
+            } else {
+                const bool in = row < n_rows;
                 // columns at or beyond k_end belong to the next slice: read them as 0
-                v = load4(A + (int64_t)row * lda, k0 + c, k_end, vec_a);
-                if (DIFF) v -= load4(A2 + (int64_t)row * lda, k0 + c, k_end, vec_a);
-                if (write_v) store4(V + (int64_t)row * ldv, k0 + c, k_end, vec_v, v);
+                r.a[i] = to_raw<TIn>(in ? load4(A + (int64_t)row * lda, col, k_end, vec_a) : zero4);
+                if (DIFF) r.a2[i] = to_raw<TIn>(in ? load4(A2 + (int64_t)row * lda, col, k_end, vec_a) : zero4);
             }
-            ra[i] = v;
         }
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
             const int idx = tid + i * kFwdThreads;
-            const int r = idx / (BK / 4), c = (idx % (BK / 4)) * 4;
-            const int row = j0 + r;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (row < J) v = load4(W + (int64_t)row * ldw, k0 + c, k_end, vec_w);
-            rb[i] = v;
+            const int row = j0 + idx / (BK / 4), col = k0 + (idx % (BK / 4)) * 4;
+            if (FAST) {
+                r.b[i] = ldg4(W + (int64_t)min(row, J - 1) * ldw + min(col, D - 4));
+            } else {
+                r.b[i] = row < J ? load4(W + (int64_t)row * ldw, col, k_end, vec_w) : zero4;
+            }
         }
     };
-    auto stage = [&]() {
+    // widen / subtract / zero out-of-range elements on the way into LDS; the workgroups of
+    // class block 0 also deliver v_i here
+    auto stage = [&](const Stage& r, int buf, int k0) {
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
             const int idx = tid + i * kFwdThreads;
-            const int r = idx / (BK / 4), c = (idx % (BK / 4)) * 4;
-            *reinterpret_cast<f32x4*>(&As[r * LS + c]) = ra[i];
+            const int rr = idx / (BK / 4), cc = (idx % (BK / 4)) * 4;
+            const int row = n0 + rr, col = k0 + cc;
+            f32x4 v = widen4(r.a[i]);
+            if (DIFF) v -= widen4(r.a2[i]);
+            const bool in = row < n_rows && col < k_end;   // FAST: k_end is a multiple of 4
+            if (FAST) v = in ? v : zero4;
+            *reinterpret_cast<f32x4*>(&As[buf * BM * LS + rr * LS + cc]) = v;
+            if (write_v && in) {
+                if (FAST) *reinterpret_cast<RawA*>(V + (int64_t)row * ldv + col) = to_raw<TIn>(v);
+                else store4(V + (int64_t)row * ldv, col, k_end, vec_v, v);
+            }
         }
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
             const int idx = tid + i * kFwdThreads;
-            const int r = idx / (BK / 4), c = (idx % (BK / 4)) * 4;
-            *reinterpret_cast<f32x4*>(&Bs[r * LS + c]) = rb[i];
+            const int rr = idx / (BK / 4), cc = (idx % (BK / 4)) * 4;
+            f32x4 v = r.b[i];
+            if (FAST) v = (j0 + rr < J && k0 + cc < k_end) ? v : zero4;
+            *reinterpret_cast<f32x4*>(&Bs[buf * BN * LS + rr * LS + cc]) = v;
         }
     };
 
@@ -106,30 +133,63 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     const int l32 = lane & 31, half = lane >> 5;
-    if (n_chunks > 0) fetch(k_begin);
-    for (int c = 0; c < n_chunks; ++c) {
-        __syncthreads();  // everyone has finished reading the previous stage
-        stage();
-        __syncthreads();
-        if (c + 1 < n_chunks) fetch(k_begin + (c + 1) * BK);
+    struct Frag { f32x4 a[MT], b[NT]; };
+    auto read_frag = [&](Frag& f, int buf, int q) {
 #pragma unroll
-        for (int q = 0; q < BK / 8; ++q) {
-            f32x4 a[MT], b[NT];
+        for (int i = 0; i < MT; ++i)
+            f.a[i] = *reinterpret_cast<const f32x4*>(
+                &As[buf * BM * LS + (wm * WM + i * 32 + l32) * LS + q * 8 + half * 4]);
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+            f.b[j] = *reinterpret_cast<const f32x4*>(
+                &Bs[buf * BN * LS + (wn * WN + j * 32 + l32) * LS + q * 8 + half * 4]);
+    };
+    auto mma_frag = [&](const Frag& f) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int i = 0; i < MT; ++i)
-                a[i] = *reinterpret_cast<const f32x4*>(&As[(wm * WM + i * 32 + l32) * LS + q * 8 + half * 4]);
 #pragma unroll
-            for (int j = 0; j < NT; ++j)
-                b[j] = *reinterpret_cast<const f32x4*>(&Bs[(wn * WN + j * 32 + l32) * LS + q * 8 + half * 4]);
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[i][r], f.b[j][r], acc[i][j], 0, 0, 0);
+    };
+    auto compute = [&](int buf) {
+        Frag f0, f1;
+        read_frag(f0, buf, 0);
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int i = 0; i < MT; ++i)
-#pragma unroll
-                    for (int j = 0; j < NT; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][r], b[j][r], acc[i][j], 0, 0, 0);
+        for (int q = 0; q < NQ; q += 2) {
+            if (q + 1 < NQ) read_frag(f1, buf, q + 1);
+            __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs they do not feed
+            mma_frag(f0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (q + 1 < NQ) {
+                if (q + 2 < NQ) read_frag(f0, buf, q + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                mma_frag(f1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
+    };
+
+    Stage r0, r1;
+    fetch(r0, k_begin);
+    fetch(r1, k_begin + BK);
+    stage(r0, 0, k_begin);
+    __syncthreads();
+    // Pair of steps (c, c+1): LDS stage 0 holds chunk c, r1 holds chunk c+1, r0 is free.
+    // One straight-line block per pair keeps every fetch two stages ahead of its use.
+    int c = 0;
+    for (; c + 1 < n_chunks; c += 2) {
+        fetch(r0, k_begin + (c + 2) * BK);
+        compute(0);
+        stage(r1, 1, k_begin + (c + 1) * BK);
+        __syncthreads();
+        fetch(r1, k_begin + (c + 3) * BK);
+        compute(1);
+        stage(r0, 0, k_begin + (c + 2) * BK);
+        __syncthreads();
     }
+    if (c < n_chunks) compute(0);   // odd count: the last chunk is already staged
 
     float* zout = Zp + (int64_t)ks * zstride;
 #pragma unroll
@@ -175,10 +235,27 @@ void finish_forward_plan(FwdPlan* p, int64_t n_rows, int64_t J, int64_t D) {
     p->grid = (int)(tiles * s);
 }
 
-template <int BM, int BN, typename TIn, bool DIFF>
-static hipError_t launch_fwd_t(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
+template <int BM, int BN, typename TIn, bool DIFF, bool FAST>
+static hipError_t launch_fwd_f(const FwdArgs& a, const FwdPlan& p, hipStream_t s, bool vec_a, bool vec_w,
+                               bool vec_v) {
     const int n_nb = (a.n_rows + BM - 1) / BM, n_jb = (a.J + BN - 1) / BN;
     const int total = n_nb * n_jb * p.split_k;
+    constexpr size_t lds_bytes = 2 * (BM + BN) * kFwdLds * sizeof(float);
+    static bool raised = false;   // opt in once to more than 64 KB of LDS per workgroup
+    if (lds_bytes > 64 * 1024 && !raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)fwd_scores_kernel<BM, BN, TIn, DIFF, FAST>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((fwd_scores_kernel<BM, BN, TIn, DIFF, FAST>), dim3(total), dim3(kFwdThreads), lds_bytes,
+                       s, (const TIn*)a.a, (const TIn*)a.a2, a.lda, a.w, a.ldw, a.zp, a.ldz, a.zstride,
+                       (TIn*)a.v, a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_nb, n_jb, total, vec_a, vec_w, vec_v);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, typename TIn, bool DIFF>
+static hipError_t launch_fwd_t(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
     const int esz = (int)sizeof(TIn);
     auto aligned = [&](const void* ptr, int64_t ld, int bytes) {
         return ptr == nullptr || (((uintptr_t)ptr % bytes) == 0 && (ld % 4) == 0);
@@ -186,11 +263,9 @@ static hipError_t launch_fwd_t(const FwdArgs& a, const FwdPlan& p, hipStream_t s
     const bool vec_a = aligned(a.a, a.lda, 4 * esz) && aligned(a.a2, a.lda, 4 * esz);
     const bool vec_w = aligned(a.w, a.ldw, 16);
     const bool vec_v = aligned(a.v, a.ldv, 4 * esz);
-    hipLaunchKernelGGL((fwd_scores_kernel<BM, BN, TIn, DIFF>), dim3(total), dim3(kFwdThreads), 0, s,
-                       (const TIn*)a.a, (const TIn*)a.a2, a.lda, a.w, a.ldw, a.zp, a.ldz, a.zstride,
-                       (TIn*)a.v, a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_nb, n_jb, total, vec_a, vec_w,
-                       vec_v);
-    return hipGetLastError();
+    const bool fast = vec_a && vec_w && vec_v && (a.D % 4) == 0 && a.D >= 4;
+    if (fast) return launch_fwd_f<BM, BN, TIn, DIFF, true>(a, p, s, vec_a, vec_w, vec_v);
+    return launch_fwd_f<BM, BN, TIn, DIFF, false>(a, p, s, vec_a, vec_w, vec_v);
 }
 
 template <typename TIn, bool DIFF>
