@@ -167,7 +167,10 @@ SFB_API int sfb_last_hip_error(const sfb_ctx *ctx);
 SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32_t *fwd_grid,
                          int32_t *recon_grid);
 /* Tuning override of the launch plan: forward tile (bm, bn in {64, 128}), split-K slices,
- * reconstruct tile variant (0: 128x128, 1: 64x128, 2: 32x128, 3: 256x128 rows x columns of W).
+ * reconstruct tile variant (rows x columns of W / wavefronts: 0: 128x128/4, 1: 64x128/2,
+ * 2: 32x128/1, 3: 256x128/4, 4: 128x128/8, 5: 64x128/4, 6: 128x128/4 with 64-row wavefronts;
+ * 4-6 split each stage's factor pairs between two wavefronts per row group; 7: 128x128/4,
+ * 8: 64x128/2, 9: 256x128/4 staged by LDS-DMA where the shape allows, else as 0, 1, 3).
  * A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
  * query sfb_workspace_bytes again.  SFB_EINVAL for a value outside the table. */
 SFB_API sfb_status sfb_set_plan(sfb_ctx *ctx, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k,

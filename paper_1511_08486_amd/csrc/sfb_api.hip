@@ -293,7 +293,7 @@ sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_
     if (!c) return SFB_EINVAL;
     if ((fwd_bm > 0 && fwd_bm != 64 && fwd_bm != 128) || (fwd_bn > 0 && fwd_bn != 64 && fwd_bn != 128))
         return SFB_EINVAL;
-    if (recon_variant > 3 || fwd_split_k > 64) return SFB_EINVAL;
+    if (recon_variant >= num_reconstruct_variants() || fwd_split_k > 64) return SFB_EINVAL;
     FwdPlan p = c->fwd_all;
     if (fwd_bm > 0) p.bm = fwd_bm;
     if (fwd_bn > 0) p.bn = fwd_bn;

@@ -65,6 +65,7 @@ struct ReconPlan {
 };
 ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N);
 ReconPlan plan_reconstruct_variant(int64_t J, int64_t D, int variant);
+int num_reconstruct_variants();
 
 struct ReconArgs {
     float* w; int64_t ldw;         // [J][ldw] read-modify-write

@@ -14,18 +14,22 @@
 // MFMA column tile t of lane l is d0 + 4*(l%32) + t, so one 128-bit LDS read feeds the
 // four column tiles and each lane ends up with four consecutive d of a W row: the W
 // read-modify-write is done with 128-bit accesses, 512 contiguous bytes per half-wave.
-// Rows are interleaved by MT the same way.
+// Rows are interleaved by MT the same way.  A workgroup is NWR row groups x KS wavefronts
+// that split every stage's factor pairs between them (KS = 2 puts two wavefronts on each
+// SIMD, so one computes while the other stages or waits at the barrier); the KS partial
+// sums are exchanged through LDS at the end and each wavefront finishes 1/KS of the rows.
 //
-// Pipeline.  One wavefront per SIMD leaves no other wavefront to hide latency behind, so
-// it is hidden in the instruction stream: factor rows are fetched from HBM/L2 two stages
-// ahead into registers, staged through a double-buffered LDS tile (one barrier per
-// stage), and the LDS operand fragments of the next four MFMA k-steps are read while the
-// current four execute.  The FAST variant has no branch around any load: out-of-range
-// rows are clamped into the matrix and zeroed by a select.
+// Pipeline.  Factor rows are fetched from HBM/L2 two stages ahead into registers as raw
+// words, staged through a double-buffered LDS tile (one barrier per stage), and the LDS
+// operand fragments of the next four MFMA k-steps are read while the current four
+// execute.  The FAST variant has no branch around any load: out-of-range rows are
+// clamped into the matrix and zeroed by a select.
 //
 // alpha is folded into U while the tile is staged (one rounding per element); the sum of
 // outer products is accumulated from zero and added to the prefetched W tile once, in the
 // epilogue.  U = 0 leaves W bit-identical.
+#include <type_traits>
+
 #include "sfb_device.h"
 #include "sfb_kernels.h"
 
@@ -37,21 +41,26 @@ constexpr int kReconGroup = 4; // MFMA k-steps (of 2 factor pairs each) per oper
 
 // FAST: every pointer 16-byte aligned (8 for bf16 V), leading dimensions multiples of 4,
 // D a multiple of 128 and J a multiple of 4 -- checked on the host.
-template <int MT, int NWAVES, typename TV, bool FAST, bool MASK>
-__global__ __launch_bounds__(NWAVES * 64) void reconstruct_apply_kernel(
+template <int MT, int NWR, int KS, typename TV, bool FAST, bool MASK>
+__global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
     float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const TV* __restrict__ V,
     int64_t ldv, int J, int D, int N, int B, float alpha, uint64_t live_mask, int n_jb, int total, bool vec_w,
     bool vec_u, bool vec_v) {
     constexpr int BK = kReconBK, BN = kReconBN, G = kReconGroup;
     constexpr int WMR = 32 * MT;            // rows per wavefront
-    constexpr int BM = WMR * NWAVES;
-    constexpr int THREADS = NWAVES * 64;
+    constexpr int BM = WMR * NWR;
+    constexpr int THREADS = NWR * KS * 64;
     constexpr int U_LD = BK * BM / 4 / THREADS;
     constexpr int V_LD = BK * BN / 4 / THREADS;
-    constexpr int NGROUPS = BK / 2 / G;
+    constexpr int SPW = BK / 2 / KS;        // MFMA k-steps per wavefront per stage
+    constexpr int NGROUPS = SPW / G;
+    constexpr int EH = 16 / KS;             // accumulator rows each wavefront finishes
     static_assert(U_LD >= 1 && V_LD >= 1, "tile too small for the thread count");
     static_assert(MT == 1 || MT == 2 || MT == 4, "row interleave must be 1, 2 or 4");
-    static_assert(NGROUPS >= 1 && NGROUPS * G * 2 == BK, "stage depth must be a multiple of the fragment group");
+    static_assert(KS == 1 || KS == 2, "one or two wavefronts per row group");
+    static_assert(NGROUPS >= 1 && NGROUPS * G * 2 * KS == BK, "stage depth must split into fragment groups");
+    static_assert(KS == 1 || 2 * BK * (BM + BN) >= NWR * KS * MT * 4 * (16 - EH) * 64,
+                  "LDS too small for the exchange of partial sums");
 
     // two stages of the U tile [BK][BM] followed by two stages of the V tile [BK][BN]
     extern __shared__ __attribute__((aligned(16))) float recon_lds[];
@@ -59,6 +68,7 @@ __global__ __launch_bounds__(NWAVES * 64) void reconstruct_apply_kernel(
     float* const Vs = recon_lds + 2 * BK * BM;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave % NWR, wk = wave / NWR;    // row group, share of the factor pairs
     const int l32 = lane & 31, half = lane >> 5;
 
     // consecutive ids walk down the J blocks of one column block, so the workgroups of a die
@@ -128,11 +138,11 @@ __global__ __launch_bounds__(NWAVES * 64) void reconstruct_apply_kernel(
 
     struct Frag { float a[G][MT]; f32x4 b[G]; };
     auto read_frag = [&](Frag& f, int buf, int g) {
-        const float* us = &Us[buf * BK * BM + wave * WMR + MT * l32];
+        const float* us = &Us[buf * BK * BM + wr * WMR + MT * l32];
         const float* vs = &Vs[buf * BK * BN + 4 * l32];
 #pragma unroll
         for (int s = 0; s < G; ++s) {
-            const int k = 2 * (g * G + s) + half;
+            const int k = 2 * (wk * SPW + g * G + s) + half;
             if constexpr (MT == 1) {
                 f.a[s][0] = us[k * BM];
             } else if constexpr (MT == 2) {
@@ -179,20 +189,22 @@ __global__ __launch_bounds__(NWAVES * 64) void reconstruct_apply_kernel(
     Stage r0, r1;
     fetch(r0, 0);
 
-    // ---- request the W tile right behind the first factor stage; it is only consumed in
-    // the epilogue.  (Starting the accumulators from W instead would add every tiny
-    // partial product to a large number and lose most of the update to rounding.) ----
-    f32x4 wreg[MT][16];
+    // ---- request this wavefront's share of the W tile right behind the first factor
+    // stage; it is only consumed in the epilogue.  (Starting the accumulators from W
+    // instead would add every tiny partial product to a large number and lose most of
+    // the update to rounding.)  Wavefront wk finishes accumulator rows [wk*EH, wk*EH+EH).
+    f32x4 wreg[MT][EH];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
+        for (int x = 0; x < EH; ++x) {
+            const int e = wk * EH + x;
             const int m = 8 * (e / 4) + 4 * half + (e % 4);
-            const int row = j0 + wave * WMR + MT * m + t;
+            const int row = j0 + wr * WMR + MT * m + t;
             if (FAST) {
-                wreg[t][e] = ldg4(W + (int64_t)min(row, J - 1) * ldw + d0 + 4 * l32);
+                wreg[t][x] = ldg4(W + (int64_t)min(row, J - 1) * ldw + d0 + 4 * l32);
             } else {
-                wreg[t][e] = row < J ? load4(W + (int64_t)row * ldw, d0 + 4 * l32, D, vec_w) : zero4;
+                wreg[t][x] = row < J ? load4(W + (int64_t)row * ldw, d0 + 4 * l32, D, vec_w) : zero4;
             }
         }
     fetch(r1, BK);
@@ -216,7 +228,229 @@ __global__ __launch_bounds__(NWAVES * 64) void reconstruct_apply_kernel(
     }
     if (c < n_chunks) compute(0);   // odd count: the last chunk is already staged
 
-    // ---- epilogue: W <- W + acc, 128-bit stores ----
+    // ---- KS = 2: swap the halves of the partial sums the partner will finish ----
+    if constexpr (KS == 2) {
+        __syncthreads();   // every wavefront is done reading the stage buffers
+        constexpr int SLOT = MT * 4 * EH * 64;                 // floats one wavefront sends
+        float* const mine = recon_lds + (wr * 2 + wk) * SLOT;        // what I receive
+        float* const theirs = recon_lds + (wr * 2 + (1 - wk)) * SLOT;   // what I send
+        auto send = [&](auto other) {
+            constexpr int O = decltype(other)::value;          // the half I give away
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int n = 0; n < 4; ++n)
+#pragma unroll
+                    for (int x = 0; x < EH; ++x)
+                        theirs[((t * 4 + n) * EH + x) * 64 + lane] = acc[t][n][O * EH + x];
+        };
+        if (wk == 0) send(std::integral_constant<int, 1>{}); else send(std::integral_constant<int, 0>{});
+        __syncthreads();
+        auto recv = [&](auto keep) {
+            constexpr int K = decltype(keep)::value;
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int n = 0; n < 4; ++n)
+#pragma unroll
+                    for (int x = 0; x < EH; ++x)
+                        acc[t][n][K * EH + x] += mine[((t * 4 + n) * EH + x) * 64 + lane];
+        };
+        if (wk == 0) recv(std::integral_constant<int, 0>{}); else recv(std::integral_constant<int, 1>{});
+    }
+
+    // ---- epilogue: W <- W + acc for this wavefront's rows, 128-bit stores ----
+    auto finish = [&](auto keep) {
+        constexpr int K = decltype(keep)::value;
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int x = 0; x < EH; ++x) {
+                constexpr int dummy = 0;
+                (void)dummy;
+                const int e = K * EH + x;
+                const int m = 8 * (e / 4) + 4 * half + (e % 4);
+                const int row = j0 + wr * WMR + MT * m + t;
+                if (row < J) {
+                    f32x4 w = wreg[t][x];
+                    w.x += acc[t][0][K * EH + x];
+                    w.y += acc[t][1][K * EH + x];
+                    w.z += acc[t][2][K * EH + x];
+                    w.w += acc[t][3][K * EH + x];
+                    if (FAST) *reinterpret_cast<f32x4*>(W + (int64_t)row * ldw + d0 + 4 * l32) = w;
+                    else store4(W + (int64_t)row * ldw, d0 + 4 * l32, D, vec_w, w);
+                }
+            }
+    };
+    if (KS == 1 || wk == 0) finish(std::integral_constant<int, 0>{});
+    else finish(std::integral_constant<int, KS - 1>{});
+}
+
+// ---------------------------------------------------------------------------------------
+// LDS-DMA variant (fp32 factors, every worker live, N a multiple of the stage depth, the
+// FAST alignment conditions): the factor tiles go from HBM/L2 straight into LDS with
+// global_load_lds_dwordx4 -- no staging registers, no LDS stores, no VALU work per stage.
+// Lane i of a wavefront-wide DMA lands at (LDS base in M0) + 16*i, which is exactly the
+// row-major [k][128] tile layout the MFMA operands are read from.  Three LDS stages form
+// a ring: while stage c is multiplied, the DMAs of stages c+1 and c+2 are in flight.  The
+// compiler does not see the DMA (inline asm), so completion is tracked by hand: the
+// vector-memory counter retires in order, `s_waitcnt vmcnt(n)` with n = the number of
+// younger DMAs this wavefront has issued means "my share of stage c has landed", and the
+// barrier that follows extends that to every wavefront's share.  The same barrier also
+// says that everyone is done reading stage c-1, which the next DMA overwrites.
+// alpha cannot be folded into U on the way in, so it is applied once in the epilogue:
+// W + alpha * acc.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_dma16(const float* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+constexpr int kDmaStages = 3;
+
+template <int MT, int NWR>
+__global__ __launch_bounds__(NWR * 64) void reconstruct_apply_dma_kernel(
+    float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const float* __restrict__ V,
+    int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total) {
+    constexpr int BK = kReconBK, BN = kReconBN, G = kReconGroup, NST = kDmaStages;
+    constexpr int WMR = 32 * MT;
+    constexpr int BM = WMR * NWR;
+    constexpr int THREADS = NWR * 64;
+    constexpr int U_LD = BK * BM / 4 / THREADS;
+    constexpr int V_LD = BK * BN / 4 / THREADS;
+    constexpr int NGROUPS = BK / 2 / G;
+    constexpr int STAGE_FLOATS = BK * (BM + BN);
+    static_assert(U_LD >= 1 && V_LD >= 1 && NGROUPS >= 1, "tile too small");
+    static_assert(U_LD + V_LD <= 32, "too many DMAs per stage for the wait encoding used");
+
+    extern __shared__ __attribute__((aligned(16))) float recon_lds[];   // NST x (U tile, V tile)
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    int id = xcd_contiguous_id(blockIdx.x, total);
+    const int jb = id % n_jb, db = id / n_jb;
+    const int j0 = jb * BM, d0 = db * BN;
+
+    // per-thread source pointers of stage 0; a stage is BK rows further down
+    const float* pu[U_LD];
+    const float* pv[V_LD];
+#pragma unroll
+    for (int i = 0; i < U_LD; ++i) {
+        const int idx = tid + i * THREADS;
+        pu[i] = U + (int64_t)(idx / (BM / 4)) * ldu + min(j0 + (idx % (BM / 4)) * 4, J - 4);
+    }
+#pragma unroll
+    for (int i = 0; i < V_LD; ++i) {
+        const int idx = tid + i * THREADS;
+        pv[i] = V + (int64_t)(idx / (BN / 4)) * ldv + d0 + (idx % (BN / 4)) * 4;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)recon_lds;
+    const int64_t ustep = (int64_t)BK * ldu, vstep = (int64_t)BK * ldv;
+
+    auto issue = [&](int chunk, int st) {
+        const uint32_t ubase =
+            __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(st * STAGE_FLOATS + wave * 64 * 4) * 4u);
+        const uint32_t vbase = ubase + (uint32_t)(BK * BM) * 4u;
+#pragma unroll
+        for (int i = 0; i < U_LD; ++i) lds_dma16(pu[i] + chunk * ustep, ubase + (uint32_t)(i * THREADS * 16));
+#pragma unroll
+        for (int i = 0; i < V_LD; ++i) lds_dma16(pv[i] + chunk * vstep, vbase + (uint32_t)(i * THREADS * 16));
+    };
+
+    f32x16 acc[MT][4];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[t][n][e] = 0.f;
+
+    struct Frag { float a[G][MT]; f32x4 b[G]; };
+    auto read_frag = [&](Frag& f, int st, int g) {
+        const float* us = &recon_lds[st * STAGE_FLOATS + wave * WMR + MT * l32];
+        const float* vs = &recon_lds[st * STAGE_FLOATS + BK * BM + 4 * l32];
+#pragma unroll
+        for (int s = 0; s < G; ++s) {
+            const int k = 2 * (g * G + s) + half;
+            if constexpr (MT == 1) {
+                f.a[s][0] = us[k * BM];
+            } else if constexpr (MT == 2) {
+                const float2 t2 = *reinterpret_cast<const float2*>(&us[k * BM]);
+                f.a[s][0] = t2.x;
+                f.a[s][1] = t2.y;
+            } else {
+                const f32x4 t4 = *reinterpret_cast<const f32x4*>(&us[k * BM]);
+#pragma unroll
+                for (int t = 0; t < MT; ++t) f.a[s][t] = t4[t];
+            }
+            f.b[s] = *reinterpret_cast<const f32x4*>(&vs[k * BN]);
+        }
+    };
+    auto mma_frag = [&](const Frag& f) {
+#pragma unroll
+        for (int s = 0; s < G; ++s)
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int n = 0; n < 4; ++n)
+                    acc[t][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[s][t], f.b[s][n], acc[t][n], 0, 0, 0);
+    };
+    auto compute = [&](int st) {
+        Frag f0, f1;
+        read_frag(f0, st, 0);
+#pragma unroll
+        for (int g = 0; g < NGROUPS; g += 2) {
+            if (g + 1 < NGROUPS) read_frag(f1, st, g + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_frag(f0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (g + 1 < NGROUPS) {
+                if (g + 2 < NGROUPS) read_frag(f0, st, g + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                mma_frag(f1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    const int n_chunks = N / BK;   // the host guarantees N % BK == 0 and N >= BK
+    issue(0, 0);
+    if (n_chunks > 1) issue(1, 1);
+
+    // the W tile: ordinary loads, consumed in the epilogue
+    f32x4 wreg[MT][16];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int m = 8 * (e / 4) + 4 * half + (e % 4);
+            const int row = j0 + wave * WMR + MT * m + t;
+            wreg[t][e] = ldg4(W + (int64_t)min(row, J - 1) * ldw + d0 + 4 * l32);
+        }
+
+    // One step: stage `st` holds chunk c once my DMAs (all but the newest stage's) have
+    // retired and everyone has passed the barrier; then refill the stage read in step c-1.
+    auto step = [&](int c, int st) {
+        if (c + 1 < n_chunks) wait_vmcnt<U_LD + V_LD>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (c + 2 < n_chunks) issue(c + 2, (st + 2) % NST);
+        compute(st);
+    };
+    // The first wait also covers the W tile loads (issued after the DMAs of chunks 0 and 1,
+    // so they are "younger" than the allowance): wait for everything once.
+    wait_vmcnt<0>();
+    int c = 0;
+    for (; c + 2 < n_chunks; c += 3) {
+        step(c, 0);
+        step(c + 1, 1);
+        step(c + 2, 2);
+    }
+    if (c < n_chunks) step(c, 0);
+    if (c + 1 < n_chunks) step(c + 1, 1);
+
 #pragma unroll
     for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -225,23 +459,56 @@ __global__ __launch_bounds__(NWAVES * 64) void reconstruct_apply_kernel(
             const int row = j0 + wave * WMR + MT * m + t;
             if (row < J) {
                 f32x4 w = wreg[t][e];
-                w.x += acc[t][0][e];
-                w.y += acc[t][1][e];
-                w.z += acc[t][2][e];
-                w.w += acc[t][3][e];
-                if (FAST) *reinterpret_cast<f32x4*>(W + (int64_t)row * ldw + d0 + 4 * l32) = w;
-                else store4(W + (int64_t)row * ldw, d0 + 4 * l32, D, vec_w, w);
+                w.x += alpha * acc[t][0][e];
+                w.y += alpha * acc[t][1][e];
+                w.z += alpha * acc[t][2][e];
+                w.w += alpha * acc[t][3][e];
+                *reinterpret_cast<f32x4*>(W + (int64_t)row * ldw + d0 + 4 * l32) = w;
             }
         }
 }
 
-struct ReconVariant { int mt, nwaves; };
+template <int MT, int NWR>
+static hipError_t launch_recon_dma(const ReconArgs& a, hipStream_t s) {
+    constexpr int BM = 32 * MT * NWR;
+    const int n_jb = (a.J + BM - 1) / BM, n_db = a.D / kReconBN;
+    const int total = n_jb * n_db;
+    constexpr size_t lds_bytes = kDmaStages * kReconBK * (BM + kReconBN) * sizeof(float);
+    static bool raised = false;
+    if (lds_bytes > 64 * 1024 && !raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_dma_kernel<MT, NWR>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((reconstruct_apply_dma_kernel<MT, NWR>), dim3(total), dim3(NWR * 64), lds_bytes, s, a.w,
+                       a.ldw, a.u, a.ldu, (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total);
+    return hipGetLastError();
+}
+
+// Shapes the DMA kernel accepts; everything else runs the register-staged kernel.
+static bool dma_ok(const ReconArgs& a) {
+    return !a.bf16 && !a.use_mask && ((uintptr_t)a.w % 16) == 0 && (a.ldw % 4) == 0 &&
+           ((uintptr_t)a.u % 16) == 0 && (a.ldu % 4) == 0 && ((uintptr_t)a.v % 16) == 0 && (a.ldv % 4) == 0 &&
+           (a.D % kReconBN) == 0 && (a.J % 4) == 0 && a.J >= 4 && (a.N % kReconBK) == 0 && a.N >= kReconBK;
+}
+
+struct ReconVariant { int mt, nwr, ks; bool dma; };
 static const ReconVariant kReconVariants[] = {
-    {1, 4},  // 128 x 128 tile, 256 threads
-    {1, 2},  // 64 x 128
-    {1, 1},  // 32 x 128
-    {2, 4},  // 256 x 128
+    {1, 4, 1, false},  // 0: 128 x 128 tile, 4 wavefronts
+    {1, 2, 1, false},  // 1: 64 x 128, 2 wavefronts
+    {1, 1, 1, false},  // 2: 32 x 128, 1 wavefront
+    {2, 4, 1, false},  // 3: 256 x 128, 4 wavefronts
+    {1, 4, 2, false},  // 4: 128 x 128, 8 wavefronts (two per SIMD)
+    {1, 2, 2, false},  // 5: 64 x 128, 4 wavefronts
+    {2, 2, 2, false},  // 6: 128 x 128, 4 wavefronts of 64 rows
+    {1, 4, 1, true},   // 7: 128 x 128, 4 wavefronts, LDS-DMA staging (falls back to 0)
+    {1, 2, 1, true},   // 8: 64 x 128, 2 wavefronts, LDS-DMA staging (falls back to 1)
+    {2, 4, 1, true},   // 9: 256 x 128, 4 wavefronts, LDS-DMA staging (falls back to 3)
 };
+constexpr int kNumReconVariants = sizeof(kReconVariants) / sizeof(kReconVariants[0]);
+
+int num_reconstruct_variants() { return kNumReconVariants; }
 
 ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
     (void)N;
@@ -249,7 +516,7 @@ ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
     const int order[] = {3, 0, 1, 2};
     int variant = 2;
     for (int v : order) {
-        const int64_t bm = 32 * kReconVariants[v].mt * kReconVariants[v].nwaves;
+        const int64_t bm = 32 * kReconVariants[v].mt * kReconVariants[v].nwr;
         const int64_t tiles = ((J + bm - 1) / bm) * ((D + kReconBN - 1) / kReconBN);
         if (tiles >= 256) { variant = v; break; }
     }
@@ -260,57 +527,71 @@ ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
 ReconPlan plan_reconstruct_variant(int64_t J, int64_t D, int variant) {
     ReconPlan p;
     p.variant = variant;
-    p.bm = 32 * kReconVariants[variant].mt * kReconVariants[variant].nwaves;
+    p.bm = 32 * kReconVariants[variant].mt * kReconVariants[variant].nwr;
     p.bn = kReconBN;
     p.grid = (int)(((J + p.bm - 1) / p.bm) * ((D + p.bn - 1) / p.bn));
     return p;
 }
 
-template <int MT, int NWAVES, typename TV, bool FAST, bool MASK>
+template <int MT, int NWR, int KS, typename TV, bool FAST, bool MASK>
 static hipError_t launch_recon_f(const ReconArgs& a, hipStream_t s, bool vec_w, bool vec_u, bool vec_v) {
-    constexpr int BM = 32 * MT * NWAVES;
+    constexpr int BM = 32 * MT * NWR;
     const int n_jb = (a.J + BM - 1) / BM, n_db = (a.D + kReconBN - 1) / kReconBN;
     const int total = n_jb * n_db;
     constexpr size_t lds_bytes = 2 * kReconBK * (BM + kReconBN) * sizeof(float);
     static bool raised = false;   // opt in once to more than 64 KB of LDS per workgroup
     if (lds_bytes > 64 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_kernel<MT, NWAVES, TV, FAST, MASK>,
+        hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_kernel<MT, NWR, KS, TV, FAST, MASK>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((reconstruct_apply_kernel<MT, NWAVES, TV, FAST, MASK>), dim3(total), dim3(NWAVES * 64),
-                       lds_bytes, s, a.w, a.ldw, a.u, a.ldu, (const TV*)a.v, a.ldv, a.J, a.D, a.N, a.B, a.alpha,
-                       a.live_mask, n_jb, total, vec_w, vec_u, vec_v);
+    hipLaunchKernelGGL((reconstruct_apply_kernel<MT, NWR, KS, TV, FAST, MASK>), dim3(total),
+                       dim3(NWR * KS * 64), lds_bytes, s, a.w, a.ldw, a.u, a.ldu, (const TV*)a.v, a.ldv, a.J, a.D,
+                       a.N, a.B, a.alpha, a.live_mask, n_jb, total, vec_w, vec_u, vec_v);
     return hipGetLastError();
 }
 
-template <int MT, int NWAVES, typename TV>
+template <int MT, int NWR, int KS, typename TV>
 static hipError_t launch_recon_t(const ReconArgs& a, hipStream_t s) {
     const bool vec_w = ((uintptr_t)a.w % 16) == 0 && (a.ldw % 4) == 0;
     const bool vec_u = ((uintptr_t)a.u % 16) == 0 && (a.ldu % 4) == 0;
     const bool vec_v = ((uintptr_t)a.v % (4 * sizeof(TV))) == 0 && (a.ldv % 4) == 0;
     const bool fast = vec_w && vec_u && vec_v && (a.D % kReconBN) == 0 && (a.J % 4) == 0 && a.J >= 4;
     if (a.use_mask) {   // a worker is missing: rare, so only the generic kernel carries the mask
-        return launch_recon_f<MT, NWAVES, TV, false, true>(a, s, vec_w, vec_u, vec_v);
+        return launch_recon_f<MT, NWR, KS, TV, false, true>(a, s, vec_w, vec_u, vec_v);
     }
-    if (fast) return launch_recon_f<MT, NWAVES, TV, true, false>(a, s, vec_w, vec_u, vec_v);
-    return launch_recon_f<MT, NWAVES, TV, false, false>(a, s, vec_w, vec_u, vec_v);
+    if (fast) return launch_recon_f<MT, NWR, KS, TV, true, false>(a, s, vec_w, vec_u, vec_v);
+    return launch_recon_f<MT, NWR, KS, TV, false, false>(a, s, vec_w, vec_u, vec_v);
 }
 
 template <typename TV>
 static hipError_t launch_recon_v(const ReconArgs& a, const ReconPlan& p, hipStream_t s) {
     switch (p.variant) {
-        case 0: return launch_recon_t<1, 4, TV>(a, s);
-        case 1: return launch_recon_t<1, 2, TV>(a, s);
-        case 2: return launch_recon_t<1, 1, TV>(a, s);
-        case 3: return launch_recon_t<2, 4, TV>(a, s);
+        case 0: return launch_recon_t<1, 4, 1, TV>(a, s);
+        case 1: return launch_recon_t<1, 2, 1, TV>(a, s);
+        case 2: return launch_recon_t<1, 1, 1, TV>(a, s);
+        case 3: return launch_recon_t<2, 4, 1, TV>(a, s);
+        case 4: return launch_recon_t<1, 4, 2, TV>(a, s);
+        case 5: return launch_recon_t<1, 2, 2, TV>(a, s);
+        case 6: return launch_recon_t<2, 2, 2, TV>(a, s);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s) {
-    return a.bf16 ? launch_recon_v<bf16_t>(a, p, s) : launch_recon_v<float>(a, p, s);
+    ReconPlan q = p;
+    if (kReconVariants[p.variant].dma) {
+        if (dma_ok(a)) {
+            switch (p.variant) {
+                case 7: return launch_recon_dma<1, 4>(a, s);
+                case 8: return launch_recon_dma<1, 2>(a, s);
+                case 9: return launch_recon_dma<2, 4>(a, s);
+            }
+        }
+        q.variant = p.variant == 7 ? 0 : (p.variant == 8 ? 1 : 3);   // same tile, register staging
+    }
+    return a.bf16 ? launch_recon_v<bf16_t>(a, q, s) : launch_recon_v<float>(a, q, s);
 }
 
 }  // namespace sfb

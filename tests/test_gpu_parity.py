@@ -52,10 +52,21 @@ def test_mlr_medium_hundred_steps(sfb):
 @pytest.mark.parametrize("plan", [dict(fwd_bm=64, fwd_bn=64, fwd_split_k=3, recon_variant=0),
                                   dict(fwd_bm=128, fwd_bn=64, fwd_split_k=1, recon_variant=2),
                                   dict(fwd_bm=64, fwd_bn=128, fwd_split_k=16, recon_variant=3),
-                                  dict(fwd_bm=128, fwd_bn=128, fwd_split_k=5, recon_variant=1)])
+                                  dict(fwd_bm=128, fwd_bn=128, fwd_split_k=5, recon_variant=1),
+                                  dict(fwd_bm=128, fwd_bn=128, fwd_split_k=2, recon_variant=4),
+                                  dict(fwd_bm=64, fwd_bn=64, fwd_split_k=2, recon_variant=5),
+                                  dict(fwd_bm=128, fwd_bn=64, fwd_split_k=7, recon_variant=6)])
 def test_every_tile_variant(sfb, plan):
     wl = workloads.make("mlr_medium", J=520, D=1000, P=4, B=50, steps=2, pool=2)
     run_chain(wl, 2, TOL32, plan=plan)
+
+
+@pytest.mark.parametrize("variant", [7, 8, 9])
+@pytest.mark.parametrize("J,D,P,B", [(520, 1024, 4, 48), (1000, 4096, 8, 64), (36, 256, 1, 32)])
+def test_lds_dma_reconstruct_variants(sfb, variant, J, D, P, B):
+    """Shapes the LDS-DMA staging accepts (D % 128 == 0, J % 4 == 0, N % 32 == 0)."""
+    wl = workloads.make("mlr_medium", seed=variant, J=J, D=D, P=P, B=B, steps=3, pool=2)
+    run_chain(wl, 3, TOL32, plan=dict(recon_variant=variant))
 
 
 def test_dml_twenty_steps(sfb):
