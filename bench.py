@@ -57,7 +57,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", default="mlr_medium")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="oracle timing budget (0 = skip)")
-    ap.add_argument("--plan", default="", help="fwd_bm,fwd_bn,split_k,recon_variant override")
+    ap.add_argument("--plan", default="", help="fwd_bm,fwd_bn,split_k,recon_variant[,fwd_dma] override")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -77,8 +77,8 @@ def main():
     wl = workloads.make(args.config)
     ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
     if args.plan:
-        bm, bn, sk, rv = [int(x) for x in args.plan.split(",")]
-        ctx.set_plan(bm, bn, sk, rv)
+        vals = [int(x) for x in args.plan.split(",")] + [-1]
+        ctx.set_plan(*vals[:5])
 
     # inputs resident in HBM before anything is timed
     vdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
@@ -127,6 +127,23 @@ def main():
     ctx.enable_timing(False)
     ctx.reset_timing()
 
+    # yardstick: a plain streaming copy, large enough (256 MiB each way) that launch and
+    # host overheads vanish; it is also the known-size kernel the HBM counters are scaled by
+    big = torch.empty(2, 64 * 1024 * 1024, dtype=torch.float32, device=dev)
+    big[0].fill_(1.0)
+    ctx.stream_copy(big[1], big[0])
+    ctx.enable_timing(True)
+    ctx.reset_timing()
+    n_other = ctx.kernel_time_ms(3)[1]
+    for _ in range(10):
+        ctx.stream_copy(big[1], big[0])
+    ms, n = ctx.kernel_time_ms(3)
+    copy_bytes = 2.0 * big[0].numel() * 4
+    copy_gbs = copy_bytes / (ms / n * 1e-3) / 1e9 if n and not n_other else None
+    ctx.enable_timing(False)
+    ctx.reset_timing()
+    del big
+
     flops = 2.0 * wl.N * wl.J * wl.D                        # per launch, scores and reconstruction alike
     dom = max((f for f in per_kernel if f in (0, 2)), key=lambda f: per_kernel[f][1])
     us = per_kernel[dom][1]
@@ -150,6 +167,8 @@ def main():
         "config": {"workload": f"{wl.name}: {wl.model} J={wl.J} D={wl.D} P={wl.P} B={wl.B} eta={wl.eta}",
                    "plan": ctx.plan_info()},
         "roofline": roofline,
+        "stream_copy": {"GB/s": copy_gbs, "bytes_per_launch": copy_bytes,
+                        "note": "plain float4 copy kernel, 256 MiB read + 256 MiB written per launch"},
     }
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)

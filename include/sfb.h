@@ -171,10 +171,16 @@ SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32
  * 2: 32x128/1, 3: 256x128/4, 4: 128x128/8, 5: 64x128/4, 6: 128x128/4 with 64-row wavefronts;
  * 4-6 split each stage's factor pairs between two wavefronts per row group; 7: 128x128/4,
  * 8: 64x128/2, 9: 256x128/4 staged by LDS-DMA where the shape allows, else as 0, 1, 3).
- * A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
+ * fwd_dma: 1 = stage the score contraction's tiles by LDS-DMA where the shape allows, 0 = always
+ * through registers, < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
  * query sfb_workspace_bytes again.  SFB_EINVAL for a value outside the table. */
 SFB_API sfb_status sfb_set_plan(sfb_ctx *ctx, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k,
-                                int32_t recon_variant);
+                                int32_t recon_variant, int32_t fwd_dma);
+/* Measurement aid, not part of the method: dst[0..bytes) = src[0..bytes) with a plain streaming
+ * kernel on the context's stream (both DEVICE, 16-byte aligned, bytes a multiple of 16; else
+ * SFB_EINVAL).  Gives the achievable copy bandwidth of the part and a known-size kernel for
+ * calibrating hardware traffic counters.  Timed under family 3. */
+SFB_API sfb_status sfb_stream_copy(sfb_ctx *ctx, void *dst, const void *src, size_t bytes);
 SFB_API sfb_status sfb_enable_timing(sfb_ctx *ctx, int enable);
 SFB_API sfb_status sfb_kernel_time_ms(sfb_ctx *ctx, int which, double *ms, int64_t *launches);
 SFB_API sfb_status sfb_reset_timing(sfb_ctx *ctx);

@@ -50,7 +50,8 @@ def _load():
         "sfb_strerror": (C.c_char_p, [C.c_int]),
         "sfb_last_hip_error": (C.c_int, [vp]),
         "sfb_plan_info": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
-        "sfb_set_plan": (C.c_int, [vp, i32, i32, i32, i32]),
+        "sfb_set_plan": (C.c_int, [vp, i32, i32, i32, i32, i32]),
+        "sfb_stream_copy": (C.c_int, [vp, vp, vp, C.c_size_t]),
         "sfb_enable_timing": (C.c_int, [vp, C.c_int]),
         "sfb_kernel_time_ms": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
         "sfb_reset_timing": (C.c_int, [vp]),
@@ -197,9 +198,14 @@ class Sfb:
         self._check(lib.sfb_plan_info(self._ctx, C.byref(a), C.byref(b), C.byref(c)), "sfb_plan_info")
         return {"fwd_split_k": a.value, "fwd_grid": b.value, "recon_grid": c.value}
 
-    def set_plan(self, fwd_bm=0, fwd_bn=0, fwd_split_k=0, recon_variant=-1):
-        self._check(lib.sfb_set_plan(self._ctx, fwd_bm, fwd_bn, fwd_split_k, recon_variant), "sfb_set_plan")
+    def set_plan(self, fwd_bm=0, fwd_bn=0, fwd_split_k=0, recon_variant=-1, fwd_dma=-1):
+        self._check(lib.sfb_set_plan(self._ctx, fwd_bm, fwd_bn, fwd_split_k, recon_variant, fwd_dma),
+                    "sfb_set_plan")
         self._ensure_workspace()
+
+    def stream_copy(self, dst, src):
+        nbytes = src.numel() * src.element_size()
+        self._check(lib.sfb_stream_copy(self._ctx, dst.data_ptr(), src.data_ptr(), nbytes), "sfb_stream_copy")
 
     def enable_timing(self, on=True):
         self._check(lib.sfb_enable_timing(self._ctx, 1 if on else 0), "sfb_enable_timing")

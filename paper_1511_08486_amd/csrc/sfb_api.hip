@@ -289,7 +289,8 @@ sfb_status sfb_plan_info(const sfb_ctx* c, int32_t* fwd_split_k, int32_t* fwd_gr
     return SFB_OK;
 }
 
-sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k, int32_t recon_variant) {
+sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k, int32_t recon_variant,
+                        int32_t fwd_dma) {
     if (!c) return SFB_EINVAL;
     if ((fwd_bm > 0 && fwd_bm != 64 && fwd_bm != 128) || (fwd_bn > 0 && fwd_bn != 64 && fwd_bn != 128))
         return SFB_EINVAL;
@@ -298,9 +299,20 @@ sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_
     if (fwd_bm > 0) p.bm = fwd_bm;
     if (fwd_bn > 0) p.bn = fwd_bn;
     if (fwd_split_k > 0) p.split_k = fwd_split_k;
+    if (fwd_dma >= 0) p.dma = fwd_dma != 0;
     finish_forward_plan(&p, (int64_t)c->P * c->B, c->J, c->D);
     c->fwd_all = p;
     if (recon_variant >= 0) c->recon = plan_reconstruct_variant(c->J, c->D, recon_variant);
+    return SFB_OK;
+}
+
+sfb_status sfb_stream_copy(sfb_ctx* c, void* dst, const void* src, size_t bytes) {
+    if (!c || !dst || !src) return SFB_EINVAL;
+    if (((uintptr_t)dst % 16) != 0 || ((uintptr_t)src % 16) != 0 || (bytes % 16) != 0) return SFB_EINVAL;
+    if (bytes == 0) return SFB_OK;
+    Timed t(c, 3);
+    hipError_t e = launch_stream_copy(src, dst, (int64_t)bytes, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e);
     return SFB_OK;
 }
 

@@ -118,6 +118,18 @@ __device__ __forceinline__ void store4(bf16_t* __restrict__ row, int64_t col, in
     }
 }
 
+// LDS-DMA: one wavefront-wide instruction moves 64 x 16 bytes from per-lane global addresses
+// to LDS; lane i lands at lds_addr + 16*i.  lds_addr must be wavefront-uniform (it travels in
+// M0).  The compiler does not see the LDS write: the caller orders it by hand with
+// wait_vmcnt (the vector-memory counter retires in order) and a barrier.
+__device__ __forceinline__ void lds_dma16(const float* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // Workgroups are handed to the 8 dies round-robin by linear id.  Renumber so that each
 // die owns one contiguous range of tile ids (tiles that share operands then share an L2).
 __device__ __forceinline__ int xcd_contiguous_id(int linear_id, int total) {

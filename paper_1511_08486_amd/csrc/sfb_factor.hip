@@ -52,16 +52,28 @@ __global__ __launch_bounds__(kFactorThreads) void factor_u_kernel(
     const int rr = live ? row : 0;
     const int label = y[rr];
 
+    // Sum the split-K slices in slice order.  The slice loop is outermost and unrolled so
+    // that several independent loads are in flight per thread; out-of-range items are
+    // clamped to column 0 (always valid) and discarded.
     f32x4 z[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int col = 4 * (t + GROUP * r);
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
-        if (live && col < J) {
-            const float* p = Zp + (int64_t)rr * ldz;       // ldz is a multiple of 4, base 16-byte aligned
-            for (int k = 0; k < split_k; ++k) s += load4(p + (int64_t)k * zstride, col, J, true);
+    for (int r = 0; r < R; ++r) z[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const float* zrow = Zp + (int64_t)rr * ldz;       // ldz is a multiple of 4, base 16-byte aligned
+#pragma unroll 4
+    for (int k = 0; k < split_k; ++k) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int col = 4 * (t + GROUP * r);
+            // a row of the workspace is padded to a multiple of 4 floats, so the whole
+            // 128-bit item is in bounds; elements at or beyond J are garbage and every
+            // use below masks them
+            const f32x4 v = ldg4(zrow + (int64_t)k * zstride + (col < J ? col : 0));
+            z[r] += (col < J) ? v : f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        z[r] = s;
+    }
+    if (!live) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) z[r] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
     float f = 0.f;
@@ -100,7 +112,7 @@ __global__ __launch_bounds__(kFactorThreads) void factor_u_kernel(
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) q += z[r][e] * z[r][e];   // columns >= J hold 0
+            for (int e = 0; e < 4; ++e) q += (4 * (t + GROUP * r) + e < J) ? z[r][e] * z[r][e] : 0.f;
         q = group_sum<GROUP>(q, red);
         const float c = (label != 0) ? 2.0f : (q < 1.0f ? -2.0f : 0.0f);
 #pragma unroll
@@ -194,8 +206,8 @@ static hipError_t launch_factor_m(const FactorArgs& a, hipStream_t s) {
                        dim3((a.n_rows + (kFactorThreads / GROUP) - 1) / (kFactorThreads / GROUP)),      \
                        dim3(kFactorThreads), 0, s, a.zp, a.ldz, a.zstride, a.split_k, a.y, a.u, a.ldu,  \
                        a.loss, a.n_rows, a.J, vec_u)
-    if (a.J <= 64 * 4 * 2) SFB_FACTOR_LAUNCH(64, 2);
-    else if (a.J <= 64 * 4 * 8) SFB_FACTOR_LAUNCH(64, 8);
+    if (a.J <= 64 * 4 * 1) SFB_FACTOR_LAUNCH(64, 1);
+    else if (a.J <= 256 * 4 * 1) SFB_FACTOR_LAUNCH(256, 1);
     else if (a.J <= 256 * 4 * 4) SFB_FACTOR_LAUNCH(256, 4);
     else if (a.J <= 256 * 4 * 12) SFB_FACTOR_LAUNCH(256, 12);
     else

@@ -205,19 +205,218 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
         }
 }
 
+// ---------------------------------------------------------------------------------------
+// LDS-DMA variant (fp32 features, no pair difference, aligned pointers, D a multiple of
+// the stage depth): feature and W tiles go from HBM/L2 straight into LDS, three stages
+// deep, with completion tracked by hand (see lds_dma16).  A tile row is 32 floats = eight
+// 16-byte items and the DMA fills LDS linearly, so the bank-conflict padding of the
+// register-staged kernel is replaced by a swizzle on the *source* side: the lane that
+// fills item slot (r, p) fetches logical item p ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 1),
+// and the fragment reads apply the same XOR.  Sixteen consecutive rows then hit sixteen
+// different 16-byte bank groups.
+// The workgroups of class block 0 copy the staged feature tile on to V.
+// ---------------------------------------------------------------------------------------
+constexpr int kFwdDmaStages = 3;
+
+__device__ __forceinline__ int fwd_swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
+template <int BM, int BN>
+__global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
+    const float* __restrict__ A, int64_t lda, const float* __restrict__ W, int64_t ldw, float* __restrict__ Zp,
+    int64_t ldz, int64_t zstride, float* __restrict__ V, int64_t ldv, int n_rows, int J, int D, int k_slice,
+    int n_nb, int n_jb, int total) {
+    constexpr int BK = kFwdBK, NST = kFwdDmaStages;
+    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int MT = WM / 32, NT = WN / 32;
+    constexpr int A_LD = BM * BK / 4 / kFwdThreads;
+    constexpr int B_LD = BN * BK / 4 / kFwdThreads;
+    constexpr int NQ = BK / 8;
+    constexpr int STAGE_FLOATS = (BM + BN) * BK;
+    static_assert(MT >= 1 && NT >= 1 && A_LD >= 1 && B_LD >= 1, "tile too small");
+
+    extern __shared__ __attribute__((aligned(16))) float fwd_lds[];   // NST x (A tile, W tile)
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    int id = xcd_contiguous_id(blockIdx.x, total);
+    const int nb = id % n_nb;
+    id /= n_nb;
+    const int jb = id % n_jb;
+    const int ks = id / n_jb;
+    const int n0 = nb * BM, j0 = jb * BN;
+    const int k_begin = ks * k_slice;
+    const int n_chunks = (min(D, k_begin + k_slice) - k_begin) / BK;   // host: D % BK == 0
+    const bool write_v = (V != nullptr) && (jb == 0);
+
+    // slot s = tid + i*256 of a tile holds row s/8, physical item s%8 = logical item ^ f(row)
+    const float* pa[A_LD];
+    const float* pb[B_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        const int s = tid + i * kFwdThreads, r = s >> 3, c = (s & 7) ^ fwd_swz(r);
+        pa[i] = A + (int64_t)min(n0 + r, n_rows - 1) * lda + k_begin + 4 * c;
+    }
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        const int s = tid + i * kFwdThreads, r = s >> 3, c = (s & 7) ^ fwd_swz(r);
+        pb[i] = W + (int64_t)min(j0 + r, J - 1) * ldw + k_begin + 4 * c;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)fwd_lds;
+    auto issue = [&](int chunk, int st) {
+        const uint32_t abase =
+            __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(st * STAGE_FLOATS + wave * 64 * 4) * 4u);
+        const uint32_t bbase = abase + (uint32_t)(BM * BK) * 4u;
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i) lds_dma16(pa[i] + chunk * BK, abase + (uint32_t)(i * kFwdThreads * 16));
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i) lds_dma16(pb[i] + chunk * BK, bbase + (uint32_t)(i * kFwdThreads * 16));
+    };
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int l32 = lane & 31, half = lane >> 5;
+    // float offsets of this lane's item for each of the NQ fragment groups (row base excluded);
+    // all of this lane's rows are congruent to l32 mod 32, so one swizzle value serves them
+    int qoff[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) qoff[q] = 4 * ((2 * q + half) ^ fwd_swz(l32));
+
+    struct Frag { f32x4 a[MT], b[NT]; };
+    auto read_frag = [&](Frag& f, int st, int q) {
+        const float* as = &fwd_lds[st * STAGE_FLOATS + (wm * WM + l32) * BK + qoff[q]];
+        const float* bs = &fwd_lds[st * STAGE_FLOATS + BM * BK + (wn * WN + l32) * BK + qoff[q]];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) f.a[i] = *reinterpret_cast<const f32x4*>(as + i * 32 * BK);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) f.b[j] = *reinterpret_cast<const f32x4*>(bs + j * 32 * BK);
+    };
+    auto mma_frag = [&](const Frag& f) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[i][r], f.b[j][r], acc[i][j], 0, 0, 0);
+    };
+    auto compute = [&](int st) {
+        Frag f0, f1;
+        read_frag(f0, st, 0);
+#pragma unroll
+        for (int q = 0; q < NQ; q += 2) {
+            if (q + 1 < NQ) read_frag(f1, st, q + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_frag(f0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (q + 1 < NQ) {
+                if (q + 2 < NQ) read_frag(f0, st, q + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                mma_frag(f1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    // v_i = a_i: pass the staged feature items on to V (class block 0 only)
+    auto copy_v = [&](int chunk, int st) {
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i) {
+            const int s = tid + i * kFwdThreads, r = s >> 3, c = (s & 7) ^ fwd_swz(r);
+            const f32x4 v = *reinterpret_cast<const f32x4*>(&fwd_lds[st * STAGE_FLOATS + 4 * s]);
+            if (n0 + r < n_rows)
+                *reinterpret_cast<f32x4*>(V + (int64_t)(n0 + r) * ldv + k_begin + chunk * BK + 4 * c) = v;
+        }
+    };
+
+    if (n_chunks > 0) issue(0, 0);
+    if (n_chunks > 1) issue(1, 1);
+    auto step = [&](int c, int st) {
+        if (c + 1 < n_chunks) wait_vmcnt<A_LD + B_LD>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (c + 2 < n_chunks) issue(c + 2, (st + 2) % NST);
+        if (write_v) copy_v(c, st);
+        compute(st);
+    };
+    int c = 0;
+    for (; c + 2 < n_chunks; c += 3) {
+        step(c, 0);
+        step(c + 1, 1);
+        step(c + 2, 2);
+    }
+    if (c < n_chunks) step(c, 0);
+    if (c + 1 < n_chunks) step(c + 1, 1);
+
+    float* zout = Zp + (int64_t)ks * zstride;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int col = j0 + wn * WN + j * 32 + l32;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = n0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                if (row < n_rows && col < J) zout[(int64_t)row * ldz + col] = acc[i][j][e];
+            }
+        }
+}
+
+template <int BM, int BN>
+static hipError_t launch_fwd_dma(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
+    const int n_nb = (a.n_rows + BM - 1) / BM, n_jb = (a.J + BN - 1) / BN;
+    const int total = n_nb * n_jb * p.split_k;
+    constexpr size_t lds_bytes = kFwdDmaStages * (BM + BN) * kFwdBK * sizeof(float);
+    static bool raised = false;
+    if (lds_bytes > 64 * 1024 && !raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)fwd_scores_dma_kernel<BM, BN>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((fwd_scores_dma_kernel<BM, BN>), dim3(total), dim3(kFwdThreads), lds_bytes, s,
+                       (const float*)a.a, a.lda, a.w, a.ldw, a.zp, a.ldz, a.zstride, (float*)a.v, a.ldv, a.n_rows,
+                       a.J, a.D, p.k_slice, n_nb, n_jb, total);
+    return hipGetLastError();
+}
+
+// Shapes the DMA kernel accepts; everything else runs the register-staged kernel.
+static bool fwd_dma_ok(const FwdArgs& a) {
+    auto al = [](const void* ptr, int64_t ld) { return ((uintptr_t)ptr % 16) == 0 && (ld % 4) == 0; };
+    return !a.bf16 && !a.diff && al(a.a, a.lda) && al(a.w, a.ldw) && (a.v == nullptr || al(a.v, a.ldv)) &&
+           (a.D % kFwdBK) == 0 && a.D >= kFwdBK;
+}
+
 FwdPlan plan_forward(int64_t n_rows, int64_t J, int64_t D) {
     FwdPlan p;
-    p.bm = 128;
-    p.bn = 128;
-    if (n_rows <= 64) p.bm = 64;
-    if (J <= 64) p.bn = 64;
-    const int64_t tiles = ((n_rows + p.bm - 1) / p.bm) * ((J + p.bn - 1) / p.bn);
+    p.dma = true;
     const int64_t chunks = (D + kFwdBK - 1) / kFwdBK;
-    // enough workgroups for two per compute unit, but never slices shorter than 4 chunks
-    int64_t s = (512 + tiles - 1) / tiles;
-    int64_t s_max = chunks / 4 > 0 ? chunks / 4 : 1;
-    if (s > s_max) s = s_max;
-    if (s > 16) s = 16;
+    // The largest tile that fills the 256 compute units with at most 4 slices of D (every
+    // slice costs a partial-sum round trip through the workspace); the smallest tile with
+    // as many slices as it takes otherwise, but never slices shorter than 4 stages.
+    const int cand[4][2] = {{128, 128}, {64, 128}, {128, 64}, {64, 64}};
+    int64_t s = 1;
+    bool found = false;
+    for (int i = 0; i < 4 && !found; ++i) {
+        const int bm = cand[i][0], bn = cand[i][1];
+        if ((n_rows <= 64 && bm > 64) || (J <= 64 && bn > 64)) continue;
+        const int64_t tiles = ((n_rows + bm - 1) / bm) * ((J + bn - 1) / bn);
+        const int64_t need = (256 + tiles - 1) / tiles;
+        if (need <= 4 && need <= (chunks / 4 > 0 ? chunks / 4 : 1)) {
+            p.bm = bm; p.bn = bn; s = need; found = true;
+        }
+    }
+    if (!found) {
+        p.bm = 64; p.bn = 64;
+        const int64_t tiles = ((n_rows + 63) / 64) * ((J + 63) / 64);
+        s = (256 + tiles - 1) / tiles;
+        const int64_t s_max = chunks / 4 > 0 ? chunks / 4 : 1;
+        if (s > s_max) s = s_max;
+        if (s > 16) s = 16;
+    }
     p.split_k = (int)s;
     finish_forward_plan(&p, n_rows, J, D);
     return p;
@@ -278,6 +477,12 @@ static hipError_t launch_fwd_tile(const FwdArgs& a, const FwdPlan& p, hipStream_
 }
 
 hipError_t launch_forward(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
+    if (p.dma && fwd_dma_ok(a)) {
+        if (p.bm == 128 && p.bn == 128) return launch_fwd_dma<128, 128>(a, p, s);
+        if (p.bm == 128 && p.bn == 64) return launch_fwd_dma<128, 64>(a, p, s);
+        if (p.bm == 64 && p.bn == 128) return launch_fwd_dma<64, 128>(a, p, s);
+        if (p.bm == 64 && p.bn == 64) return launch_fwd_dma<64, 64>(a, p, s);
+    }
     if (a.bf16) {
         if (a.diff) return hipErrorInvalidValue;
         return launch_fwd_tile<bf16_t, false>(a, p, s);

@@ -14,6 +14,7 @@ struct FwdPlan {
     int split_k;     // slices of the D-long contraction
     int k_slice;     // columns of D per slice (multiple of the K chunk)
     int grid;        // workgroups
+    bool dma;        // stage tiles by LDS-DMA where the shape allows
 };
 
 // Chooses tile and split for Z[n_rows][J] = A W^T with contraction length D.
@@ -57,6 +58,9 @@ struct DensifyArgs {
     int64_t nnz;          // length of col / val
 };
 hipError_t launch_csr_densify(const DensifyArgs& a, hipStream_t s);
+
+// dst[0 .. bytes) = src[0 .. bytes); both 16-byte aligned, bytes a multiple of 16.
+hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
 
 struct ReconPlan {
     int variant;          // index into the tile table

@@ -301,14 +301,6 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
 // alpha cannot be folded into U on the way in, so it is applied once in the epilogue:
 // W + alpha * acc.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ void lds_dma16(const float* g, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 constexpr int kDmaStages = 3;
 
 template <int MT, int NWR>
@@ -512,8 +504,10 @@ int num_reconstruct_variants() { return kNumReconVariants; }
 
 ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
     (void)N;
-    // largest tile that still gives every compute unit a workgroup; the smallest otherwise
-    const int order[] = {3, 0, 1, 2};
+    // largest tile that still gives every compute unit a workgroup; the smallest otherwise.
+    // 7 and 8 are the LDS-DMA forms of the 128- and 64-row tiles (they fall back to the
+    // register-staged kernel by themselves when the shape does not allow DMA).
+    const int order[] = {7, 8, 2};
     int variant = 2;
     for (int v : order) {
         const int64_t bm = 32 * kReconVariants[v].mt * kReconVariants[v].nwr;

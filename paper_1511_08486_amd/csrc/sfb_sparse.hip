@@ -36,3 +36,25 @@ hipError_t launch_csr_densify(const DensifyArgs& a, hipStream_t s) {
 }
 
 }  // namespace sfb
+
+namespace sfb {
+
+// Plain streaming copy: the yardstick for "what does a kernel that only moves bytes reach
+// on this part", and the known-size kernel the HBM traffic counters are calibrated on.
+__global__ __launch_bounds__(256) void stream_copy_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst,
+                                                          int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStream_t s) {
+    const int64_t n16 = bytes / 16;
+    int64_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const f32x4*)src, (f32x4*)dst,
+                       n16);
+    return hipGetLastError();
+}
+
+}  // namespace sfb

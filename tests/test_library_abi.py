@@ -87,7 +87,7 @@ def test_calls_reject_bad_arguments_before_launching(lib):
     assert lib.sfb_reconstruct_apply(ctx, fake, 16, fake, 8, fake, 16, float("nan"), 1.0, None) == -1
     assert lib.sfb_step(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None, float("inf"), None) == -1
     # plan override outside the table
-    assert lib.sfb_set_plan(ctx, 96, 0, 0, -1) == -1 and lib.sfb_set_plan(ctx, 0, 0, 0, 99) == -1
+    assert lib.sfb_set_plan(ctx, 96, 0, 0, -1, -1) == -1 and lib.sfb_set_plan(ctx, 0, 0, 0, 99, -1) == -1
     lib.sfb_destroy(ctx)
     # a mask needs P <= 64
     assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 8, 16, 65, 1, sfb.SFB_F32, None) == 0
