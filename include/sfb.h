@@ -102,9 +102,11 @@ SFB_API sfb_status sfb_create(sfb_ctx **out, sfb_model m, int64_t J, int64_t D, 
                       sfb_dtype input_dtype, void *hip_stream);
 SFB_API void sfb_destroy(sfb_ctx *ctx);
 
-/* Bytes of device workspace the factor computation needs (scores Z[N][J] as split-K
- * partial sums).  The caller allocates at least that many bytes, 16-byte aligned, and
- * registers them; the library uses the buffer until it is replaced or the ctx destroyed. */
+/* Bytes of device workspace the context needs: the scores Z[N][J] as split-K partial sums,
+ * plus, for bf16 contexts, the transposed bf16 copies of the factors that the
+ * reconstruction multiplies (so sfb_reconstruct_apply needs the workspace too).  The caller
+ * allocates at least that many bytes, 256-byte aligned, and registers them; the library
+ * uses the buffer until it is replaced or the ctx destroyed. */
 SFB_API sfb_status sfb_workspace_bytes(const sfb_ctx *ctx, size_t *bytes);
 SFB_API sfb_status sfb_set_workspace(sfb_ctx *ctx, void *dev, size_t bytes);
 

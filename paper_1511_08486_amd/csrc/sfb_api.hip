@@ -25,6 +25,7 @@ struct sfb_ctx {
     sfb_dtype dtype;
     hipStream_t stream;
     FwdPlan fwd_all, fwd_worker;   // scores of all N rows / of one worker's B rows
+    FwdPlan fwd_bf16;              // all N rows on the bf16 matrix cores (bf16 contexts)
     ReconPlan recon;
     void* ws;
     size_t ws_bytes;
@@ -37,11 +38,24 @@ namespace {
 
 inline int64_t round_up4(int64_t x) { return (x + 3) / 4 * 4; }
 
-size_t workspace_need(const sfb_ctx* c) {
+// Bytes of split-K partial scores (the first region of the workspace), rounded to 256.
+size_t scores_need(const sfb_ctx* c) {
     const int64_t ldz = round_up4(c->J);
-    const size_t all = (size_t)c->fwd_all.split_k * (size_t)c->P * c->B * ldz * sizeof(float);
+    size_t need = (size_t)c->fwd_all.split_k * (size_t)c->P * c->B * ldz * sizeof(float);
     const size_t one = (size_t)c->fwd_worker.split_k * (size_t)c->B * ldz * sizeof(float);
-    return all > one ? all : one;
+    if (one > need) need = one;
+    if (c->dtype == SFB_BF16) {
+        const size_t bf = (size_t)c->fwd_bf16.split_k * (size_t)c->P * c->B * ldz * sizeof(float);
+        if (bf > need) need = bf;
+    }
+    return (need + 255) / 256 * 256;
+}
+
+// bf16 contexts append the transposed bf16 factors of the reconstruction.
+size_t workspace_need(const sfb_ctx* c) {
+    size_t need = scores_need(c);
+    if (c->dtype == SFB_BF16) need += bf16_recon_workspace(c->J, c->D, (int64_t)c->P * c->B);
+    return need;
 }
 
 sfb_status hip_fail(sfb_ctx* c, hipError_t e) {
@@ -121,13 +135,16 @@ sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t
         f.a = b->a; f.a2 = (c->model == SFB_DML) ? b->a2 : nullptr; f.lda = b->lda;
         f.v = v_rows; f.ldv = ldv; f.diff = (c->model == SFB_DML);
     }
+    // bf16 features, full batch, aligned: the bf16 matrix-core kernel with its own plan
+    const bool on_bf16_cores = bf16 && n_rows == c->P * c->B && n_rows >= 128 && forward_bf16_ok(f);
+    const FwdPlan& used = on_bf16_cores ? c->fwd_bf16 : plan;
     {
         Timed t(c, 0);
-        hipError_t e = launch_forward(f, plan, c->stream);
+        hipError_t e = on_bf16_cores ? launch_forward_bf16(f, used, c->stream) : launch_forward(f, used, c->stream);
         if (e != hipSuccess) return hip_fail(c, e);
     }
     FactorArgs g{};
-    g.zp = (const float*)c->ws; g.ldz = ldz; g.zstride = f.zstride; g.split_k = plan.split_k;
+    g.zp = (const float*)c->ws; g.ldz = ldz; g.zstride = f.zstride; g.split_k = used.split_k;
     g.y = y; g.u = U + row0 * ldu; g.ldu = ldu; g.loss = loss ? loss + row0 : nullptr;
     g.n_rows = n_rows; g.J = (int)c->J; g.model = (Model)c->model;
     {
@@ -163,7 +180,13 @@ sfb_status recon_launch(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64
         r.use_mask = !all;
     }
     Timed t(c, 2);
-    hipError_t e = launch_reconstruct(r, c->recon, c->stream);
+    hipError_t e;
+    if (r.bf16) {
+        if (c->ws == nullptr || c->ws_bytes < workspace_need(c)) return SFB_EWORKSPACE;
+        e = launch_reconstruct_bf16(r, (char*)c->ws + scores_need(c), c->stream);
+    } else {
+        e = launch_reconstruct(r, c->recon, c->stream);
+    }
     if (e != hipSuccess) return hip_fail(c, e);
     return SFB_OK;
 }
@@ -188,6 +211,7 @@ sfb_status sfb_create(sfb_ctx** out, sfb_model m, int64_t J, int64_t D, int32_t 
     c->stream = (hipStream_t)hip_stream;
     c->fwd_all = plan_forward((int64_t)P * B, J, D);
     c->fwd_worker = plan_forward(B, J, D);
+    c->fwd_bf16 = plan_forward_bf16((int64_t)P * B, J, D);
     c->recon = plan_reconstruct(J, D, (int64_t)P * B);
     c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->timing = false;
     *out = c;
@@ -210,7 +234,7 @@ sfb_status sfb_workspace_bytes(const sfb_ctx* c, size_t* bytes) {
 
 sfb_status sfb_set_workspace(sfb_ctx* c, void* dev, size_t bytes) {
     if (!c || !dev) return SFB_EINVAL;
-    if (((uintptr_t)dev % 16) != 0) return SFB_EINVAL;
+    if (((uintptr_t)dev % 256) != 0) return SFB_EINVAL;
     if (bytes < workspace_need(c)) return SFB_EWORKSPACE;
     c->ws = dev; c->ws_bytes = bytes;
     return SFB_OK;

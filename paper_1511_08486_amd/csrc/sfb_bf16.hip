@@ -1,0 +1,356 @@
+// bf16-feature path (bf16 a_i and v_i, fp32 W, u and accumulation) on the bf16 matrix cores.
+//
+// With 16x the fp32 MFMA rate, both contractions of the step stop being compute-bound at
+// the sizes this path is for (W of hundreds of MB): the score pass must read W once, the
+// reconstruction must read and write it once, and everything else is sized so that HBM
+// streaming of W is the only thing that cannot be hidden.
+//
+// One "NT" kernel serves both contractions: C[m][n] = sum_k A[m][k] * B[n][k] with both
+// operands contiguous along k, staged HBM/L2 -> LDS by DMA through a ring of stages
+// (completion tracked by hand, see lds_dma16), swizzled on the source side so that the
+// 128-bit fragment reads are conflict-free, and v_mfma_f32_32x32x16_bf16 (lane l supplies
+// 8 consecutive k of row l%32, lanes 32..63 the upper 8 of each 16; A and B use the same
+// k order, so the order itself is immaterial).
+//   scores (Section 2, z = W a):      A = features [N][D] bf16, B = W [J][D] fp32, widened
+//                                     operand rounded to bf16 (RNE) after the LDS read;
+//                                     epilogue stores a split-K partial of Z and, for class
+//                                     block 0, passes the feature tile on to V (v_i = a_i).
+//   reconstruct (Section 3 + 2.1):    A = (alpha u)^T [J][N] bf16, B = v^T [D][N] bf16, both
+//                                     produced by transpose_pack_kernel from the received
+//                                     factors; epilogue is the read-modify-write W += C.
+#include "sfb_device.h"
+#include "sfb_kernels.h"
+
+namespace sfb {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBfBM = 256, kBfBN = 128, kBfBK = 32;
+constexpr int kBfThreads = 256;
+
+__device__ __forceinline__ void lds_dma16_raw(const void* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+}
+
+// swizzles: a bf16 tile row is 4 items of 16 bytes, an fp32 tile row 8 items
+__device__ __forceinline__ int swz4(int r) { return (r >> 2) & 3; }
+__device__ __forceinline__ int swz8(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
+enum BfEpilogue { kStoreZ = 0, kUpdateW = 1 };
+
+// B_FP32: B rows are fp32 in memory (W in the score pass) and are rounded to bf16 after the
+// LDS read.  NST: stages in the ring.
+template <bool B_FP32, int EPI, int NST>
+__global__ __launch_bounds__(kBfThreads) void nt_bf16_kernel(
+    const bf16_t* __restrict__ A, int64_t lda, const void* __restrict__ Bv, int64_t ldb, float* __restrict__ C,
+    int64_t ldc, int64_t cstride, bf16_t* __restrict__ Vout, int64_t ldv, int M, int N, int K, int k_slice,
+    int n_mb, int n_nb, int total) {
+    constexpr int BM = kBfBM, BN = kBfBN, BK = kBfBK;
+    constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
+    constexpr int A_ITEMS = BM * 4, B_ITEMS = BN * (B_FP32 ? 8 : 4);
+    constexpr int A_LD = A_ITEMS / kBfThreads, B_LD = B_ITEMS / kBfThreads;
+    constexpr int A_BYTES = A_ITEMS * 16, STAGE_BYTES = (A_ITEMS + B_ITEMS) * 16;
+    constexpr int KSTEPS = BK / 16;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char bf_lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    // consecutive ids share the B block (W rows in the score pass: the workgroups that
+    // reuse a W block run next to each other on one die)
+    int id = xcd_contiguous_id(blockIdx.x, total);
+    const int mb = id % n_mb;
+    id /= n_mb;
+    const int nb = id % n_nb;
+    const int ks = id / n_nb;
+    const int m0 = mb * BM, n0 = nb * BN;
+    const int k_begin = ks * k_slice;
+    const int n_chunks = (min(K, k_begin + k_slice) - k_begin) / BK;   // host: K % BK == 0
+
+    const bf16_t* pa[A_LD];
+    const unsigned char* pb[B_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        const int s = tid + i * kBfThreads, r = s >> 2, c = (s & 3) ^ swz4(r);
+        pa[i] = A + (int64_t)min(m0 + r, M - 1) * lda + k_begin + 8 * c;
+    }
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        const int s = tid + i * kBfThreads;
+        if (B_FP32) {
+            const int r = s >> 3, c = (s & 7) ^ swz8(r);
+            pb[i] = (const unsigned char*)((const float*)Bv + (int64_t)min(n0 + r, N - 1) * ldb + k_begin + 4 * c);
+        } else {
+            const int r = s >> 2, c = (s & 3) ^ swz4(r);
+            pb[i] = (const unsigned char*)((const bf16_t*)Bv + (int64_t)min(n0 + r, N - 1) * ldb + k_begin + 8 * c);
+        }
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)bf_lds;
+    auto issue = [&](int chunk, int st) {
+        const uint32_t abase = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(st * STAGE_BYTES + wave * 1024));
+        const uint32_t bbase = abase + (uint32_t)A_BYTES;
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i) lds_dma16_raw(pa[i] + chunk * BK, abase + (uint32_t)(i * kBfThreads * 16));
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i)
+            lds_dma16_raw(pb[i] + (int64_t)chunk * BK * (B_FP32 ? 4 : 2), bbase + (uint32_t)(i * kBfThreads * 16));
+    };
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // byte offsets of this lane's items (row base excluded); every row this lane reads is
+    // congruent to l32 modulo 32, so the swizzle value is a lane constant
+    int a_off[KSTEPS], b_off[KSTEPS];
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) {
+        a_off[s] = 16 * ((2 * s + half) ^ swz4(l32));
+        b_off[s] = B_FP32 ? 16 * ((4 * s + 2 * half) ^ swz8(l32)) : 16 * ((2 * s + half) ^ swz4(l32));
+    }
+    const int sw8 = swz8(l32);
+
+    struct Frag { u32x4 a[MT]; u32x4 b[NT]; u32x4 b2[B_FP32 ? NT : 1]; };
+    auto read_frag = [&](Frag& f, int st, int s) {
+        const unsigned char* as = bf_lds + st * STAGE_BYTES + (wm * WM + l32) * 64;
+        const unsigned char* bs = bf_lds + st * STAGE_BYTES + A_BYTES + (wn * WN + l32) * (B_FP32 ? 128 : 64);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(as + i * 32 * 64 + a_off[s]);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            if (B_FP32) {
+                // 8 consecutive k of an fp32 row = two 16-byte items (logical 4s+2h and 4s+2h+1)
+                const unsigned char* row = bs + j * 32 * 128;
+                f.b[j] = *reinterpret_cast<const u32x4*>(row + b_off[s]);
+                f.b2[j] = *reinterpret_cast<const u32x4*>(row + 16 * ((4 * s + 2 * half + 1) ^ sw8));
+            } else {
+                f.b[j] = *reinterpret_cast<const u32x4*>(bs + j * 32 * 64 + b_off[s]);
+            }
+        }
+    };
+    auto mma_frag = [&](const Frag& f) {
+        bf16x8 bop[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            if (B_FP32) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    bop[j][e] = (__bf16)__uint_as_float(f.b[j][e]);          // round to nearest even
+                    bop[j][e + 4] = (__bf16)__uint_as_float(f.b2[j][e]);
+                }
+            } else {
+                bop[j] = __builtin_bit_cast(bf16x8, f.b[j]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]), bop[j],
+                                                                     acc[i][j], 0, 0, 0);
+    };
+    auto compute = [&](int st) {
+        Frag f0, f1;
+        read_frag(f0, st, 0);
+#pragma unroll
+        for (int s = 0; s < KSTEPS; s += 2) {
+            if (s + 1 < KSTEPS) read_frag(f1, st, s + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_frag(f0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (s + 1 < KSTEPS) {
+                if (s + 2 < KSTEPS) read_frag(f0, st, s + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                mma_frag(f1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    // v_i = a_i: the staged feature items go on to V (score pass, class block 0 only)
+    const bool write_v = (EPI == kStoreZ) && (Vout != nullptr) && (nb == 0);
+    auto copy_v = [&](int chunk, int st) {
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i) {
+            const int s = tid + i * kBfThreads, r = s >> 2, c = (s & 3) ^ swz4(r);
+            const u32x4 v = *reinterpret_cast<const u32x4*>(bf_lds + st * STAGE_BYTES + 16 * s);
+            if (m0 + r < M)
+                *reinterpret_cast<u32x4*>(Vout + (int64_t)(m0 + r) * ldv + k_begin + chunk * BK + 8 * c) = v;
+        }
+    };
+
+    // ring of NST stages, NST-1 of them in flight ahead of the one being multiplied
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p)
+        if (p < n_chunks) issue(p, p);
+    auto step = [&](int c, int st) {
+        // younger DMAs that may still be in flight: those of the next NST-2 chunks
+        const int younger = min(n_chunks - 1 - c, NST - 2);
+        if (younger >= 2) wait_vmcnt<2 * (A_LD + B_LD)>();
+        else if (younger == 1) wait_vmcnt<A_LD + B_LD>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (c + NST - 1 < n_chunks) issue(c + NST - 1, (st + NST - 1) % NST);
+        if (write_v) copy_v(c, st);
+        compute(st);
+    };
+    static_assert(NST == 3 || NST == 4, "ring depth");
+    int c = 0;
+    for (; c + NST - 1 < n_chunks; c += NST) {
+        step(c, 0);
+        step(c + 1, 1);
+        step(c + 2, 2);
+        if (NST == 4) step(c + 3, 3);
+    }
+    if (c < n_chunks) step(c, 0);
+    if (c + 1 < n_chunks) step(c + 1, 1);
+    if (NST == 4 && c + 2 < n_chunks) step(c + 2, 2);
+
+    float* cout = C + (int64_t)ks * cstride;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int col = n0 + wn * WN + j * 32 + l32;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                if (row < M && col < N) {
+                    float* p = cout + (int64_t)row * ldc + col;
+                    if (EPI == kUpdateW) *p = *p + acc[i][j][e];
+                    else *p = acc[i][j][e];
+                }
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------
+// Received factors -> the k-contiguous bf16 operands of the reconstruction:
+//   UT[j][n] = bf16(alpha * U[n][j]),  VT[d][n] = V[n][d],  n < ldn (zero beyond N and for
+//   the rows of dead workers).  64 x 64 tiles through LDS; blocks [0, n_ub) do U, the rest V.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void transpose_pack_kernel(
+    const float* __restrict__ U, int64_t ldu, const bf16_t* __restrict__ V, int64_t ldv, bf16_t* __restrict__ UT,
+    bf16_t* __restrict__ VT, int64_t ldn, int N, int J, int D, int B, float alpha, uint64_t live_mask,
+    bool use_mask, int n_jblk, int n_dblk) {
+    __shared__ __attribute__((aligned(16))) bf16_t tile[64][72];   // [column of the source][n], 144-byte rows
+    const int tid = threadIdx.x;
+    const int n_cblk = n_jblk + n_dblk;
+    const int cb = blockIdx.x % n_cblk, kb = blockIdx.x / n_cblk;
+    const bool is_u = cb < n_jblk;
+    const int c0 = (is_u ? cb : cb - n_jblk) * 64, k0 = kb * 64;
+    const int ncols = is_u ? J : D;
+    // load 64 (n) x 64 (columns): thread -> 4 rows x 4 consecutive columns
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int n = k0 + (tid >> 4) + 16 * i, c = c0 + (tid & 15) * 4;
+        bool live = n < N;
+        if (use_mask && live) live = (live_mask >> (n / B)) & 1ull;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (live) {
+            if (is_u) v = load4(U + (int64_t)n * ldu, c, ncols, false) * alpha;
+            else v = load4(V + (int64_t)n * ldv, c, ncols, false);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tile[(tid & 15) * 4 + e][(tid >> 4) + 16 * i] = f32_to_bf16(v[e]);
+    }
+    __syncthreads();
+    // store: thread -> 2 columns x 8 consecutive n (16 bytes)
+    bf16_t* out = is_u ? UT : VT;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = (tid >> 3) + 32 * i, n8 = (tid & 7) * 8;
+        if (c0 + c < ncols && k0 + n8 < ldn)
+            *reinterpret_cast<u32x4*>(out + (int64_t)(c0 + c) * ldn + k0 + n8) =
+                *reinterpret_cast<const u32x4*>(&tile[c][n8]);
+    }
+}
+
+int64_t bf16_ldn(int64_t N) { return (N + 63) / 64 * 64; }
+
+// Device scratch the bf16 reconstruction needs: (alpha u)^T [J][ldn] and v^T [D][ldn], bf16,
+// each rounded up to 256 bytes.
+size_t bf16_recon_workspace(int64_t J, int64_t D, int64_t N) {
+    const size_t ldn = (size_t)bf16_ldn(N);
+    auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+    return up((size_t)J * ldn * 2) + up((size_t)D * ldn * 2);
+}
+
+hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s) {
+    const int64_t ldn = bf16_ldn(a.N);
+    auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+    bf16_t* UT = (bf16_t*)ws;
+    bf16_t* VT = (bf16_t*)((char*)ws + up((size_t)a.J * ldn * 2));
+    const int n_jblk = (a.J + 63) / 64, n_dblk = (a.D + 63) / 64, n_kblk = (int)(ldn / 64);
+    hipLaunchKernelGGL(transpose_pack_kernel, dim3((n_jblk + n_dblk) * n_kblk), dim3(256), 0, s, a.u, a.ldu,
+                       (const bf16_t*)a.v, a.ldv, UT, VT, ldn, a.N, a.J, a.D, a.B, a.alpha, a.live_mask, a.use_mask,
+                       n_jblk, n_dblk);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    constexpr int NST = 3;
+    constexpr size_t lds_bytes = (size_t)NST * (kBfBM * 4 + kBfBN * 4) * 16;
+    static bool raised = false;
+    if (lds_bytes > 64 * 1024 && !raised) {
+        e = hipFuncSetAttribute((const void*)nt_bf16_kernel<false, kUpdateW, NST>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    const int n_mb = (a.J + kBfBM - 1) / kBfBM, n_nb = (a.D + kBfBN - 1) / kBfBN;
+    const int total = n_mb * n_nb;
+    hipLaunchKernelGGL((nt_bf16_kernel<false, kUpdateW, NST>), dim3(total), dim3(kBfThreads), lds_bytes, s, UT, ldn,
+                       (const void*)VT, ldn, a.w, a.ldw, (int64_t)0, (bf16_t*)nullptr, (int64_t)0, a.J, a.D,
+                       (int)ldn, (int)ldn, n_mb, n_nb, total);
+    return hipGetLastError();
+}
+
+bool forward_bf16_ok(const FwdArgs& a) {
+    return a.bf16 && !a.diff && ((uintptr_t)a.a % 16) == 0 && (a.lda % 8) == 0 && ((uintptr_t)a.w % 16) == 0 &&
+           (a.ldw % 4) == 0 && (a.v == nullptr || (((uintptr_t)a.v % 16) == 0 && (a.ldv % 8) == 0)) &&
+           (a.D % kBfBK) == 0 && a.D >= kBfBK;
+}
+
+FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D) {
+    FwdPlan p;
+    p.dma = true;
+    p.bm = kBfBM;
+    p.bn = kBfBN;
+    const int64_t tiles = ((n_rows + kBfBM - 1) / kBfBM) * ((J + kBfBN - 1) / kBfBN);
+    const int64_t chunks = D / kBfBK > 0 ? D / kBfBK : 1;
+    int64_t s = (256 + tiles - 1) / tiles;
+    const int64_t s_max = chunks / 8 > 0 ? chunks / 8 : 1;
+    if (s > s_max) s = s_max;
+    if (s > 16) s = 16;
+    const int64_t per = (chunks + s - 1) / s;
+    s = (chunks + per - 1) / per;
+    p.split_k = (int)s;
+    p.k_slice = (int)(per * kBfBK);
+    p.grid = (int)(tiles * s);
+    return p;
+}
+
+hipError_t launch_forward_bf16(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
+    constexpr int NST = 4;
+    constexpr size_t lds_bytes = (size_t)NST * (kBfBM * 4 + kBfBN * 8) * 16;
+    static bool raised = false;
+    if (lds_bytes > 64 * 1024 && !raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)nt_bf16_kernel<true, kStoreZ, NST>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    const int n_mb = (a.n_rows + kBfBM - 1) / kBfBM, n_nb = (a.J + kBfBN - 1) / kBfBN;
+    const int total = n_mb * n_nb * p.split_k;
+    hipLaunchKernelGGL((nt_bf16_kernel<true, kStoreZ, NST>), dim3(total), dim3(kBfThreads), lds_bytes, s,
+                       (const bf16_t*)a.a, a.lda, (const void*)a.w, a.ldw, a.zp, a.ldz, a.zstride, (bf16_t*)a.v,
+                       a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_mb, n_nb, total);
+    return hipGetLastError();
+}
+
+}  // namespace sfb

@@ -83,4 +83,12 @@ struct ReconArgs {
 };
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s);
 
+// bf16-feature path on the bf16 matrix cores (sfb_bf16.hip)
+bool forward_bf16_ok(const FwdArgs& a);                       // alignment / shape the DMA kernel needs
+FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D);
+hipError_t launch_forward_bf16(const FwdArgs& a, const FwdPlan& p, hipStream_t s);
+size_t bf16_recon_workspace(int64_t J, int64_t D, int64_t N);  // bytes of device scratch
+// ws: bf16_recon_workspace bytes, 256-byte aligned.  Two launches: transpose/pack, then W += C.
+hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s);
+
 }  // namespace sfb

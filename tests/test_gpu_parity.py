@@ -113,6 +113,33 @@ def test_bf16_ragged(sfb):
     run_chain(wl, 2, TOLBF)
 
 
+@pytest.mark.parametrize("J,D,P,B", [(300, 1024, 4, 40), (130, 96, 2, 64), (1000, 2048, 8, 64)])
+def test_bf16_matrix_core_path(sfb, J, D, P, B):
+    """Shapes that take the bf16 MFMA kernels (D % 32 == 0, N >= 128, aligned rows)."""
+    wl = workloads.make("mlr_large", seed=J, J=J, D=D, P=P, B=B, steps=3, pool=2)
+    run_chain(wl, 3, TOLBF)
+
+
+def test_bf16_dead_worker_and_plain_sum(sfb):
+    wl = workloads.make("mlr_large", seed=9, J=260, D=512, P=4, B=48, steps=1, pool=1)
+    dev = "cuda:0"
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype="bf16", device=dev)
+    b = wl.batch(0)
+    db, dy = to_device(wl, b, dev)
+    W = torch.from_numpy(wl.W0).to(dev)
+    U, V, loss = alloc_factors(wl, dev)
+    ctx.compute_factors(W, db, dy, U, V, loss)
+    active = [1, 0, 1, 1]
+    U[wl.B:2 * wl.B] = float("nan")                     # a dead worker's slot may hold anything
+    ctx.reconstruct_apply(W, U, V, eta=0.2, scale=1.0, active=active)
+    ctx.sync()
+    Uo, Vo, fo = oracle.factors(wl.model, wl.W0, b)
+    want = oracle.apply_update(wl.W0, oracle.delta_w(Uo, Vo, wl.P, wl.B, active) * wl.B, 0.2)
+    assert_close(W.cpu().numpy(), want, TOLBF, "W, bf16, dead worker")
+    assert np.array_equal(V.float().cpu().numpy(), b["A"])
+    ctx.close()
+
+
 def test_worker_calls_equal_batched_call_and_mask_drops_a_worker(sfb):
     wl = workloads.make("mlr_medium", J=200, D=520, P=4, B=24, steps=1, pool=1)
     dev = "cuda:0"

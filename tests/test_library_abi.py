@@ -82,7 +82,7 @@ def test_calls_reject_bad_arguments_before_launching(lib):
     # no workspace registered yet
     assert lib.sfb_compute_factors(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None) == -5
     assert lib.sfb_set_workspace(ctx, fake, 1) == -5
-    assert lib.sfb_set_workspace(ctx, C.c_void_p(0x1004), 1 << 20) == -1      # not 16-byte aligned
+    assert lib.sfb_set_workspace(ctx, C.c_void_p(0x1010), 1 << 20) == -1      # not 256-byte aligned
     # non-finite learning rate
     assert lib.sfb_reconstruct_apply(ctx, fake, 16, fake, 8, fake, 16, float("nan"), 1.0, None) == -1
     assert lib.sfb_step(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None, float("inf"), None) == -1
