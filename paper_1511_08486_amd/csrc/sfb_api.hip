@@ -307,8 +307,9 @@ int sfb_last_hip_error(const sfb_ctx* c) { return c ? c->last_hip : 0; }
 
 sfb_status sfb_plan_info(const sfb_ctx* c, int32_t* fwd_split_k, int32_t* fwd_grid, int32_t* recon_grid) {
     if (!c) return SFB_EINVAL;
-    if (fwd_split_k) *fwd_split_k = c->fwd_all.split_k;
-    if (fwd_grid) *fwd_grid = c->fwd_all.grid;
+    const FwdPlan& f = c->dtype == SFB_BF16 ? c->fwd_bf16 : c->fwd_all;
+    if (fwd_split_k) *fwd_split_k = f.split_k;
+    if (fwd_grid) *fwd_grid = f.grid;
     if (recon_grid) *recon_grid = c->recon.grid;
     return SFB_OK;
 }

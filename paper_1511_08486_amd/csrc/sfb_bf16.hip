@@ -62,10 +62,23 @@ __global__ __launch_bounds__(kBfThreads) void nt_bf16_kernel(
     // consecutive ids share the B block (W rows in the score pass: the workgroups that
     // reuse a W block run next to each other on one die)
     int id = xcd_contiguous_id(blockIdx.x, total);
-    const int mb = id % n_mb;
-    id /= n_mb;
-    const int nb = id % n_nb;
-    const int ks = id / n_nb;
+    int mb, nb, ks;
+    if (EPI == kUpdateW) {
+        // one slice; walk the tile grid in bands of 8 B-blocks with the A block fastest
+        // inside a band: a band's 8 B-blocks (1 MB) stay in the die's L2 while the A blocks
+        // stream past them once per band
+        constexpr int BAND = 8;
+        ks = 0;
+        const int band = id / (BAND * n_mb), rem = id - band * BAND * n_mb;
+        const int width = min(BAND, n_nb - band * BAND);     // the last band may be narrower
+        nb = band * BAND + rem % width;
+        mb = rem / width;
+    } else {
+        mb = id % n_mb;
+        id /= n_mb;
+        nb = id % n_nb;
+        ks = id / n_nb;
+    }
     const int m0 = mb * BM, n0 = nb * BN;
     const int k_begin = ks * k_slice;
     const int n_chunks = (min(K, k_begin + k_slice) - k_begin) / BK;   // host: K % BK == 0
@@ -189,6 +202,24 @@ __global__ __launch_bounds__(kBfThreads) void nt_bf16_kernel(
 #pragma unroll
     for (int p = 0; p < NST - 1; ++p)
         if (p < n_chunks) issue(p, p);
+
+    // reconstruction: request the whole W tile now (clamped addresses, no branches); it is
+    // consumed in the epilogue, so HBM latency and the tile's read both hide under the MFMAs
+    float wreg[EPI == kUpdateW ? MT : 1][EPI == kUpdateW ? NT : 1][16];
+    if (EPI == kUpdateW) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int cc = min(n0 + wn * WN + j * 32 + l32, N - 1);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                    wreg[i][j][e] = C[(int64_t)min(row, M - 1) * ldc + cc];
+                }
+            }
+        wait_vmcnt<0>();   // these loads are younger than the DMAs above: settle the count once
+    }
     auto step = [&](int c, int st) {
         // younger DMAs that may still be in flight: those of the next NST-2 chunks
         const int younger = min(n_chunks - 1 - c, NST - 2);
@@ -218,13 +249,17 @@ __global__ __launch_bounds__(kBfThreads) void nt_bf16_kernel(
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const int col = n0 + wn * WN + j * 32 + l32;
+            if (EPI == kUpdateW) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                if (row < M && col < N) {
-                    float* p = cout + (int64_t)row * ldc + col;
-                    if (EPI == kUpdateW) *p = *p + acc[i][j][e];
-                    else *p = acc[i][j][e];
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                    if (row < M && col < N) cout[(int64_t)row * ldc + col] = wreg[i][j][e] + acc[i][j][e];
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                    if (row < M && col < N) cout[(int64_t)row * ldc + col] = acc[i][j][e];
                 }
             }
         }
@@ -323,10 +358,18 @@ FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D) {
     p.bn = kBfBN;
     const int64_t tiles = ((n_rows + kBfBM - 1) / kBfBM) * ((J + kBfBN - 1) / kBfBN);
     const int64_t chunks = D / kBfBK > 0 ? D / kBfBK : 1;
-    int64_t s = (256 + tiles - 1) / tiles;
-    const int64_t s_max = chunks / 8 > 0 ? chunks / 8 : 1;
-    if (s > s_max) s = s_max;
-    if (s > 16) s = 16;
+    // One workgroup per compute unit is resident (the stage ring fills the LDS), so the time
+    // goes as rounds-of-256 x 1/slices: take the slice count that wastes the fewest rounds,
+    // charging a little for every extra partial-sum round trip.
+    const int64_t s_max = chunks / 8 > 0 ? (chunks / 8 < 8 ? chunks / 8 : 8) : 1;
+    int64_t best = 1;
+    double best_cost = 1e30;
+    for (int64_t s = 1; s <= s_max; ++s) {
+        const double rounds = (double)((tiles * s + 255) / 256);
+        const double cost = rounds / (double)s + 0.02 * (double)s;
+        if (cost < best_cost - 1e-12) { best_cost = cost; best = s; }
+    }
+    int64_t s = best;
     const int64_t per = (chunks + s - 1) / s;
     s = (chunks + per - 1) / per;
     p.split_k = (int)s;
