@@ -173,8 +173,9 @@ SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32
  * 2: 32x128/1, 3: 256x128/4, 4: 128x128/8, 5: 64x128/4, 6: 128x128/4 with 64-row wavefronts;
  * 4-6 split each stage's factor pairs between two wavefronts per row group; 7: 128x128/4,
  * 8: 64x128/2, 9: 256x128/4 staged by LDS-DMA where the shape allows, else as 0, 1, 3).
- * fwd_dma: 1 = stage the score contraction's tiles by LDS-DMA where the shape allows, 0 = always
- * through registers, < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
+ * fwd_dma: bit 0 = stage the score contraction's tiles by LDS-DMA where the shape allows (else
+ * always through registers); bit 1 = L2SVM scores by the dense contraction on the densified rows
+ * instead of from the CSR entries; < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
  * query sfb_workspace_bytes again.  SFB_EINVAL for a value outside the table. */
 SFB_API sfb_status sfb_set_plan(sfb_ctx *ctx, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k,
                                 int32_t recon_variant, int32_t fwd_dma);

@@ -31,6 +31,7 @@ struct sfb_ctx {
     size_t ws_bytes;
     int last_hip;
     bool timing;
+    bool sparse_forward;           // L2SVM: scores from the CSR entries when W rows fit in LDS
     std::vector<EventPair> used[kFamilies], spare;
 };
 
@@ -122,15 +123,25 @@ sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t
     f.zp = (float*)c->ws; f.ldz = ldz; f.zstride = (int64_t)n_rows * ldz;
     f.n_rows = n_rows; f.J = (int)c->J; f.D = (int)c->D;
     f.bf16 = bf16;
+    bool sparse_scores = false;
     if (c->model == SFB_L2SVM) {
-        // v_i first: the dense rows then feed the score contraction as its A operand.
+        // v_i first: the dense rows are what the reconstruction multiplies
         DensifyArgs d{b->csr_rowptr, b->csr_col, b->csr_val, (float*)v_rows, ldv, n_rows, (int)c->D, b->nnz};
         {
             Timed t(c, 3);
             hipError_t e = launch_csr_densify(d, c->stream);
             if (e != hipSuccess) return hip_fail(c, e);
         }
-        f.a = v_rows; f.a2 = nullptr; f.lda = ldv; f.v = nullptr; f.ldv = 0; f.diff = false;
+        if (c->sparse_forward && csr_scores_ok((int)c->D)) {
+            // scores from the stored entries only: 2*nnz*J flops instead of 2*N*J*D
+            Timed t(c, 0);
+            hipError_t e = launch_csr_scores(d, W, ldw, (float*)c->ws, ldz, (int)c->J, c->stream);
+            if (e != hipSuccess) return hip_fail(c, e);
+            sparse_scores = true;
+        } else {
+            // fall back to the dense contraction on the densified rows
+            f.a = v_rows; f.a2 = nullptr; f.lda = ldv; f.v = nullptr; f.ldv = 0; f.diff = false;
+        }
     } else {
         f.a = b->a; f.a2 = (c->model == SFB_DML) ? b->a2 : nullptr; f.lda = b->lda;
         f.v = v_rows; f.ldv = ldv; f.diff = (c->model == SFB_DML);
@@ -138,13 +149,13 @@ sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t
     // bf16 features, full batch, aligned: the bf16 matrix-core kernel with its own plan
     const bool on_bf16_cores = bf16 && n_rows == c->P * c->B && n_rows >= 128 && forward_bf16_ok(f);
     const FwdPlan& used = on_bf16_cores ? c->fwd_bf16 : plan;
-    {
+    if (!sparse_scores) {
         Timed t(c, 0);
         hipError_t e = on_bf16_cores ? launch_forward_bf16(f, used, c->stream) : launch_forward(f, used, c->stream);
         if (e != hipSuccess) return hip_fail(c, e);
     }
     FactorArgs g{};
-    g.zp = (const float*)c->ws; g.ldz = ldz; g.zstride = f.zstride; g.split_k = used.split_k;
+    g.zp = (const float*)c->ws; g.ldz = ldz; g.zstride = f.zstride; g.split_k = sparse_scores ? 1 : used.split_k;
     g.y = y; g.u = U + row0 * ldu; g.ldu = ldu; g.loss = loss ? loss + row0 : nullptr;
     g.n_rows = n_rows; g.J = (int)c->J; g.model = (Model)c->model;
     {
@@ -213,7 +224,7 @@ sfb_status sfb_create(sfb_ctx** out, sfb_model m, int64_t J, int64_t D, int32_t 
     c->fwd_worker = plan_forward(B, J, D);
     c->fwd_bf16 = plan_forward_bf16((int64_t)P * B, J, D);
     c->recon = plan_reconstruct(J, D, (int64_t)P * B);
-    c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->timing = false;
+    c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->timing = false; c->sparse_forward = true;
     *out = c;
     return SFB_OK;
 }
@@ -325,6 +336,7 @@ sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_
     if (fwd_bn > 0) p.bn = fwd_bn;
     if (fwd_split_k > 0) p.split_k = fwd_split_k;
     if (fwd_dma >= 0) p.dma = fwd_dma != 0;
+    if (fwd_dma >= 0) c->sparse_forward = (fwd_dma & 2) == 0;   // bit 1 set: dense scores for CSR input
     finish_forward_plan(&p, (int64_t)c->P * c->B, c->J, c->D);
     c->fwd_all = p;
     if (recon_variant >= 0) c->recon = plan_reconstruct_variant(c->J, c->D, recon_variant);

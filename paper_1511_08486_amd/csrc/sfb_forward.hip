@@ -220,9 +220,11 @@ constexpr int kFwdDmaStages = 3;
 
 __device__ __forceinline__ int fwd_swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
-template <int BM, int BN>
+// DIFF (pair models, Section 2 DML): the second point of each pair is staged next to the
+// first and a = x - y is formed when a fragment (or the V copy) is read from LDS.
+template <int BM, int BN, bool DIFF>
 __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
-    const float* __restrict__ A, int64_t lda, const float* __restrict__ W, int64_t ldw, float* __restrict__ Zp,
+    const float* __restrict__ A, const float* __restrict__ A2, int64_t lda, const float* __restrict__ W, int64_t ldw, float* __restrict__ Zp,
     int64_t ldz, int64_t zstride, float* __restrict__ V, int64_t ldv, int n_rows, int J, int D, int k_slice,
     int n_nb, int n_jb, int total) {
     constexpr int BK = kFwdBK, NST = kFwdDmaStages;
@@ -231,10 +233,11 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
     constexpr int A_LD = BM * BK / 4 / kFwdThreads;
     constexpr int B_LD = BN * BK / 4 / kFwdThreads;
     constexpr int NQ = BK / 8;
-    constexpr int STAGE_FLOATS = (BM + BN) * BK;
+    constexpr int A2_FLOATS = DIFF ? BM * BK : 0;      // second-point tile sits after the W tile
+    constexpr int STAGE_FLOATS = (BM + BN) * BK + A2_FLOATS;
     static_assert(MT >= 1 && NT >= 1 && A_LD >= 1 && B_LD >= 1, "tile too small");
 
-    extern __shared__ __attribute__((aligned(16))) float fwd_lds[];   // NST x (A tile, W tile)
+    extern __shared__ __attribute__((aligned(16))) float fwd_lds[];   // NST x (A tile, W tile[, A2 tile])
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -250,6 +253,8 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
 
     // slot s = tid + i*256 of a tile holds row s/8, physical item s%8 = logical item ^ f(row)
     const float* pa[A_LD];
+    int64_t a2_delta = 0;                 // A2 - A in elements: the two points share lda
+    if (DIFF) a2_delta = A2 - A;
     const float* pb[B_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
@@ -270,7 +275,14 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
         for (int i = 0; i < A_LD; ++i) lds_dma16(pa[i] + chunk * BK, abase + (uint32_t)(i * kFwdThreads * 16));
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) lds_dma16(pb[i] + chunk * BK, bbase + (uint32_t)(i * kFwdThreads * 16));
+        if (DIFF) {
+            const uint32_t a2base = bbase + (uint32_t)(BN * BK) * 4u;
+#pragma unroll
+            for (int i = 0; i < A_LD; ++i)
+                lds_dma16(pa[i] + a2_delta + chunk * BK, a2base + (uint32_t)(i * kFwdThreads * 16));
+        }
     };
+    constexpr int DMAS = A_LD + B_LD + (DIFF ? A_LD : 0);   // per thread per stage
 
     f32x16 acc[MT][NT];
 #pragma unroll
@@ -292,7 +304,10 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
         const float* as = &fwd_lds[st * STAGE_FLOATS + (wm * WM + l32) * BK + qoff[q]];
         const float* bs = &fwd_lds[st * STAGE_FLOATS + BM * BK + (wn * WN + l32) * BK + qoff[q]];
 #pragma unroll
-        for (int i = 0; i < MT; ++i) f.a[i] = *reinterpret_cast<const f32x4*>(as + i * 32 * BK);
+        for (int i = 0; i < MT; ++i) {
+            f.a[i] = *reinterpret_cast<const f32x4*>(as + i * 32 * BK);
+            if (DIFF) f.a[i] -= *reinterpret_cast<const f32x4*>(as + (BM + BN) * BK + i * 32 * BK);
+        }
 #pragma unroll
         for (int j = 0; j < NT; ++j) f.b[j] = *reinterpret_cast<const f32x4*>(bs + j * 32 * BK);
     };
@@ -327,7 +342,8 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
             const int s = tid + i * kFwdThreads, r = s >> 3, c = (s & 7) ^ fwd_swz(r);
-            const f32x4 v = *reinterpret_cast<const f32x4*>(&fwd_lds[st * STAGE_FLOATS + 4 * s]);
+            f32x4 v = *reinterpret_cast<const f32x4*>(&fwd_lds[st * STAGE_FLOATS + 4 * s]);
+            if (DIFF) v -= *reinterpret_cast<const f32x4*>(&fwd_lds[st * STAGE_FLOATS + (BM + BN) * BK + 4 * s]);
             if (n0 + r < n_rows)
                 *reinterpret_cast<f32x4*>(V + (int64_t)(n0 + r) * ldv + k_begin + chunk * BK + 4 * c) = v;
         }
@@ -336,7 +352,7 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
     if (n_chunks > 0) issue(0, 0);
     if (n_chunks > 1) issue(1, 1);
     auto step = [&](int c, int st) {
-        if (c + 1 < n_chunks) wait_vmcnt<A_LD + B_LD>(); else wait_vmcnt<0>();
+        if (c + 1 < n_chunks) wait_vmcnt<DMAS>(); else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
         if (c + 2 < n_chunks) issue(c + 2, (st + 2) % NST);
         if (write_v) copy_v(c, st);
@@ -365,20 +381,20 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
         }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool DIFF>
 static hipError_t launch_fwd_dma(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
     const int n_nb = (a.n_rows + BM - 1) / BM, n_jb = (a.J + BN - 1) / BN;
     const int total = n_nb * n_jb * p.split_k;
-    constexpr size_t lds_bytes = kFwdDmaStages * (BM + BN) * kFwdBK * sizeof(float);
+    constexpr size_t lds_bytes = kFwdDmaStages * (BM + BN + (DIFF ? BM : 0)) * kFwdBK * sizeof(float);
     static bool raised = false;
     if (lds_bytes > 64 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)fwd_scores_dma_kernel<BM, BN>,
+        hipError_t e = hipFuncSetAttribute((const void*)fwd_scores_dma_kernel<BM, BN, DIFF>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((fwd_scores_dma_kernel<BM, BN>), dim3(total), dim3(kFwdThreads), lds_bytes, s,
-                       (const float*)a.a, a.lda, a.w, a.ldw, a.zp, a.ldz, a.zstride, (float*)a.v, a.ldv, a.n_rows,
+    hipLaunchKernelGGL((fwd_scores_dma_kernel<BM, BN, DIFF>), dim3(total), dim3(kFwdThreads), lds_bytes, s,
+                       (const float*)a.a, (const float*)a.a2, a.lda, a.w, a.ldw, a.zp, a.ldz, a.zstride, (float*)a.v, a.ldv, a.n_rows,
                        a.J, a.D, p.k_slice, n_nb, n_jb, total);
     return hipGetLastError();
 }
@@ -386,38 +402,37 @@ static hipError_t launch_fwd_dma(const FwdArgs& a, const FwdPlan& p, hipStream_t
 // Shapes the DMA kernel accepts; everything else runs the register-staged kernel.
 static bool fwd_dma_ok(const FwdArgs& a) {
     auto al = [](const void* ptr, int64_t ld) { return ((uintptr_t)ptr % 16) == 0 && (ld % 4) == 0; };
-    return !a.bf16 && !a.diff && al(a.a, a.lda) && al(a.w, a.ldw) && (a.v == nullptr || al(a.v, a.ldv)) &&
-           (a.D % kFwdBK) == 0 && a.D >= kFwdBK;
+    return !a.bf16 && al(a.a, a.lda) && (!a.diff || al(a.a2, a.lda)) && al(a.w, a.ldw) &&
+           (a.v == nullptr || al(a.v, a.ldv)) && (a.D % kFwdBK) == 0 && a.D >= kFwdBK;
 }
 
 FwdPlan plan_forward(int64_t n_rows, int64_t J, int64_t D) {
     FwdPlan p;
     p.dma = true;
     const int64_t chunks = (D + kFwdBK - 1) / kFwdBK;
-    // The largest tile that fills the 256 compute units with at most 4 slices of D (every
-    // slice costs a partial-sum round trip through the workspace); the smallest tile with
-    // as many slices as it takes otherwise, but never slices shorter than 4 stages.
+    // Small cost model, in microseconds.  A compute unit multiplies at a fixed rate whatever
+    // the number of resident workgroups, so the contraction takes
+    //     rounds-of-256-workgroups x (flops of one workgroup) / (rate of one compute unit),
+    // smaller tiles pay a little more LDS traffic per flop, and every slice of D costs one
+    // write and one read of a partial Z through the workspace.
     const int cand[4][2] = {{128, 128}, {64, 128}, {128, 64}, {64, 64}};
-    int64_t s = 1;
-    bool found = false;
-    for (int i = 0; i < 4 && !found; ++i) {
+    const double tile_penalty[4] = {1.00, 1.03, 1.08, 1.12};
+    const double cu_flops_per_us = 0.65 * 256.0 * 2400.0;              // ~65 % of 256 flop/clk at 2.4 GHz
+    const double partial_us = (double)n_rows * (double)J * 8.0 / 3.0e6; // 8 bytes per score at ~3 TB/s
+    const int64_t s_max = chunks / 4 > 0 ? (chunks / 4 < 16 ? chunks / 4 : 16) : 1;
+    double best = 1e300;
+    p.bm = 64; p.bn = 64; p.split_k = 1;
+    for (int i = 0; i < 4; ++i) {
         const int bm = cand[i][0], bn = cand[i][1];
         if ((n_rows <= 64 && bm > 64) || (J <= 64 && bn > 64)) continue;
         const int64_t tiles = ((n_rows + bm - 1) / bm) * ((J + bn - 1) / bn);
-        const int64_t need = (256 + tiles - 1) / tiles;
-        if (need <= 4 && need <= (chunks / 4 > 0 ? chunks / 4 : 1)) {
-            p.bm = bm; p.bn = bn; s = need; found = true;
+        for (int64_t s = 1; s <= s_max; ++s) {
+            const double rounds = (double)((tiles * s + 255) / 256);
+            const double wg_flops = 2.0 * bm * bn * (double)((chunks + s - 1) / s * kFwdBK);
+            const double us = tile_penalty[i] * rounds * wg_flops / cu_flops_per_us + partial_us * (double)s;
+            if (us < best * (1.0 - 1e-9)) { best = us; p.bm = bm; p.bn = bn; p.split_k = (int)s; }
         }
     }
-    if (!found) {
-        p.bm = 64; p.bn = 64;
-        const int64_t tiles = ((n_rows + 63) / 64) * ((J + 63) / 64);
-        s = (256 + tiles - 1) / tiles;
-        const int64_t s_max = chunks / 4 > 0 ? chunks / 4 : 1;
-        if (s > s_max) s = s_max;
-        if (s > 16) s = 16;
-    }
-    p.split_k = (int)s;
     finish_forward_plan(&p, n_rows, J, D);
     return p;
 }
@@ -478,10 +493,16 @@ static hipError_t launch_fwd_tile(const FwdArgs& a, const FwdPlan& p, hipStream_
 
 hipError_t launch_forward(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
     if (p.dma && fwd_dma_ok(a)) {
-        if (p.bm == 128 && p.bn == 128) return launch_fwd_dma<128, 128>(a, p, s);
-        if (p.bm == 128 && p.bn == 64) return launch_fwd_dma<128, 64>(a, p, s);
-        if (p.bm == 64 && p.bn == 128) return launch_fwd_dma<64, 128>(a, p, s);
-        if (p.bm == 64 && p.bn == 64) return launch_fwd_dma<64, 64>(a, p, s);
+        if (a.diff) {   // 128 x 128 with a second feature tile would not leave room for three stages
+            if (p.bm == 64 && p.bn == 128) return launch_fwd_dma<64, 128, true>(a, p, s);
+            if (p.bm == 128 && p.bn == 64) return launch_fwd_dma<128, 64, true>(a, p, s);
+            if (p.bm == 64 && p.bn == 64) return launch_fwd_dma<64, 64, true>(a, p, s);
+        } else {
+            if (p.bm == 128 && p.bn == 128) return launch_fwd_dma<128, 128, false>(a, p, s);
+            if (p.bm == 128 && p.bn == 64) return launch_fwd_dma<128, 64, false>(a, p, s);
+            if (p.bm == 64 && p.bn == 128) return launch_fwd_dma<64, 128, false>(a, p, s);
+            if (p.bm == 64 && p.bn == 64) return launch_fwd_dma<64, 64, false>(a, p, s);
+        }
     }
     if (a.bf16) {
         if (a.diff) return hipErrorInvalidValue;

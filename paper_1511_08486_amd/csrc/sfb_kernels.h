@@ -59,6 +59,12 @@ struct DensifyArgs {
 };
 hipError_t launch_csr_densify(const DensifyArgs& a, hipStream_t s);
 
+// Scores straight from the CSR features (no dense A): Z[n][j] = sum_e val[e] * W[j][col[e]].
+// Usable when four W rows fit in LDS (csr_scores_ok); writes one slice (no split-K).
+bool csr_scores_ok(int D);
+hipError_t launch_csr_scores(const DensifyArgs& a, const float* W, int64_t ldw, float* Z, int64_t ldz, int J,
+                             hipStream_t s);
+
 // dst[0 .. bytes) = src[0 .. bytes); both 16-byte aligned, bytes a multiple of 16.
 hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
 

@@ -87,7 +87,8 @@ def test_l2svm_twenty_steps(sfb):
     print("l2svm worst error/allowance", worst)
 
 
-def test_l2svm_ragged_and_empty_rows(sfb):
+@pytest.mark.parametrize("dense_scores", [False, True])
+def test_l2svm_ragged_and_empty_rows(sfb, dense_scores):
     wl = workloads.make("l2svm", seed=3, J=77, D=501, P=3, B=11, steps=2, density=0.05)
     # make two rows empty and one row a single entry
     for b in wl.batches:
@@ -98,7 +99,12 @@ def test_l2svm_ragged_and_empty_rows(sfb):
         keep = np.concatenate([np.arange(r * per, r * per + counts[r]) for r in range(wl.N)]).astype(np.int64)
         b["col"], b["val"] = b["col"][keep], b["val"][keep]
         b["rowptr"] = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
-    run_chain(wl, 2, TOL32)
+    run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else None)
+
+
+def test_l2svm_dense_score_fallback_full_size(sfb):
+    wl = workloads.make("l2svm", pool=2)
+    run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3))
 
 
 @pytest.mark.timeout(900)
