@@ -301,13 +301,13 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
 // alpha cannot be folded into U on the way in, so it is applied once in the epilogue:
 // W + alpha * acc.
 // ---------------------------------------------------------------------------------------
-constexpr int kDmaStages = 3;
 
-template <int MT, int NWR>
+// BK factor pairs per stage, NST stages in the ring (NST - 1 of them in flight ahead).
+template <int MT, int NWR, int BK, int NST>
 __global__ __launch_bounds__(NWR * 64) void reconstruct_apply_dma_kernel(
     float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const float* __restrict__ V,
     int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total) {
-    constexpr int BK = kReconBK, BN = kReconBN, G = kReconGroup, NST = kDmaStages;
+    constexpr int BN = kReconBN, G = kReconGroup;
     constexpr int WMR = 32 * MT;
     constexpr int BM = WMR * NWR;
     constexpr int THREADS = NWR * 64;
@@ -409,10 +409,24 @@ __global__ __launch_bounds__(NWR * 64) void reconstruct_apply_dma_kernel(
     };
 
     const int n_chunks = N / BK;   // the host guarantees N % BK == 0 and N >= BK
-    issue(0, 0);
-    if (n_chunks > 1) issue(1, 1);
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p)
+        if (p < n_chunks) issue(p, p);
 
-    // the W tile: ordinary loads, consumed in the epilogue
+    // One step: stage `st` holds chunk c once my DMAs (all but the newest stage's) have
+    // retired and everyone has passed the barrier; then refill the stage read in step c-1.
+    auto step = [&](int c, int st) {
+        const int younger = min(n_chunks - 1 - c, NST - 2);   // chunks issued after chunk c
+        if (younger >= 1) wait_vmcnt<U_LD + V_LD>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (c + NST - 1 < n_chunks) issue(c + NST - 1, (st + NST - 1) % NST);
+        compute(st);
+    };
+    static_assert(NST == 2 || NST == 3, "ring depth");
+    // Chunk 0 first, with nothing else competing for HBM; the W tile is requested right
+    // after it (ordinary loads, consumed in the epilogue), so its read overlaps the
+    // remaining stages instead of delaying the first MFMA.
+    step(0, 0);
     f32x4 wreg[MT][16];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
@@ -423,25 +437,14 @@ __global__ __launch_bounds__(NWR * 64) void reconstruct_apply_dma_kernel(
             wreg[t][e] = ldg4(W + (int64_t)min(row, J - 1) * ldw + d0 + 4 * l32);
         }
 
-    // One step: stage `st` holds chunk c once my DMAs (all but the newest stage's) have
-    // retired and everyone has passed the barrier; then refill the stage read in step c-1.
-    auto step = [&](int c, int st) {
-        if (c + 1 < n_chunks) wait_vmcnt<U_LD + V_LD>(); else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
-        if (c + 2 < n_chunks) issue(c + 2, (st + 2) % NST);
-        compute(st);
-    };
-    // The first wait also covers the W tile loads (issued after the DMAs of chunks 0 and 1,
-    // so they are "younger" than the allowance): wait for everything once.
-    wait_vmcnt<0>();
-    int c = 0;
-    for (; c + 2 < n_chunks; c += 3) {
-        step(c, 0);
-        step(c + 1, 1);
-        step(c + 2, 2);
+    int c = 1;
+    for (; c + NST - 1 < n_chunks; c += NST) {
+        step(c, 1 % NST);
+        step(c + 1, 2 % NST);
+        if (NST == 3) step(c + 2, 0);
     }
-    if (c < n_chunks) step(c, 0);
-    if (c + 1 < n_chunks) step(c + 1, 1);
+    if (c < n_chunks) step(c, 1 % NST);
+    if (NST == 3 && c + 1 < n_chunks) step(c + 1, 2);
 
 #pragma unroll
     for (int t = 0; t < MT; ++t)
@@ -460,29 +463,29 @@ __global__ __launch_bounds__(NWR * 64) void reconstruct_apply_dma_kernel(
         }
 }
 
-template <int MT, int NWR>
+template <int MT, int NWR, int BK, int NST>
 static hipError_t launch_recon_dma(const ReconArgs& a, hipStream_t s) {
     constexpr int BM = 32 * MT * NWR;
     const int n_jb = (a.J + BM - 1) / BM, n_db = a.D / kReconBN;
     const int total = n_jb * n_db;
-    constexpr size_t lds_bytes = kDmaStages * kReconBK * (BM + kReconBN) * sizeof(float);
+    constexpr size_t lds_bytes = (size_t)NST * BK * (BM + kReconBN) * sizeof(float);
     static bool raised = false;
     if (lds_bytes > 64 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_dma_kernel<MT, NWR>,
+        hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_dma_kernel<MT, NWR, BK, NST>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((reconstruct_apply_dma_kernel<MT, NWR>), dim3(total), dim3(NWR * 64), lds_bytes, s, a.w,
+    hipLaunchKernelGGL((reconstruct_apply_dma_kernel<MT, NWR, BK, NST>), dim3(total), dim3(NWR * 64), lds_bytes, s, a.w,
                        a.ldw, a.u, a.ldu, (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total);
     return hipGetLastError();
 }
 
 // Shapes the DMA kernel accepts; everything else runs the register-staged kernel.
-static bool dma_ok(const ReconArgs& a) {
+static bool dma_ok(const ReconArgs& a, int bk) {
     return !a.bf16 && !a.use_mask && ((uintptr_t)a.w % 16) == 0 && (a.ldw % 4) == 0 &&
            ((uintptr_t)a.u % 16) == 0 && (a.ldu % 4) == 0 && ((uintptr_t)a.v % 16) == 0 && (a.ldv % 4) == 0 &&
-           (a.D % kReconBN) == 0 && (a.J % 4) == 0 && a.J >= 4 && (a.N % kReconBK) == 0 && a.N >= kReconBK;
+           (a.D % kReconBN) == 0 && (a.J % 4) == 0 && a.J >= 4 && (a.N % bk) == 0 && a.N >= bk;
 }
 
 struct ReconVariant { int mt, nwr, ks; bool dma; };
@@ -497,6 +500,7 @@ static const ReconVariant kReconVariants[] = {
     {1, 4, 1, true},   // 7: 128 x 128, 4 wavefronts, LDS-DMA staging (falls back to 0)
     {1, 2, 1, true},   // 8: 64 x 128, 2 wavefronts, LDS-DMA staging (falls back to 1)
     {2, 4, 1, true},   // 9: 256 x 128, 4 wavefronts, LDS-DMA staging (falls back to 3)
+    {1, 4, 1, true},   // 10: as 7 with 64-pair stages, two-stage ring (falls back to 0)
 };
 constexpr int kNumReconVariants = sizeof(kReconVariants) / sizeof(kReconVariants[0]);
 
@@ -576,14 +580,15 @@ static hipError_t launch_recon_v(const ReconArgs& a, const ReconPlan& p, hipStre
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s) {
     ReconPlan q = p;
     if (kReconVariants[p.variant].dma) {
-        if (dma_ok(a)) {
+        if (dma_ok(a, p.variant == 10 ? 64 : kReconBK)) {
             switch (p.variant) {
-                case 7: return launch_recon_dma<1, 4>(a, s);
-                case 8: return launch_recon_dma<1, 2>(a, s);
-                case 9: return launch_recon_dma<2, 4>(a, s);
+                case 7: return launch_recon_dma<1, 4, kReconBK, 3>(a, s);
+                case 8: return launch_recon_dma<1, 2, kReconBK, 3>(a, s);
+                case 9: return launch_recon_dma<2, 4, kReconBK, 3>(a, s);
+                case 10: return launch_recon_dma<1, 4, 64, 2>(a, s);
             }
         }
-        q.variant = p.variant == 7 ? 0 : (p.variant == 8 ? 1 : 3);   // same tile, register staging
+        q.variant = p.variant == 8 ? 1 : (p.variant == 9 ? 3 : 0);   // same tile, register staging
     }
     return a.bf16 ? launch_recon_v<bf16_t>(a, q, s) : launch_recon_v<float>(a, q, s);
 }
