@@ -22,8 +22,7 @@ if ROOT not in sys.path:
 
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix-core peak
 PEAK_HBM_GBS = 8000.0
-FAMILIES = {0: "scores (fwd_scores_kernel)", 1: "factor u (factor_u_kernel)",
-            2: "reconstruct-apply (reconstruct_apply_kernel)", 3: "csr densify"}
+FAMILIES = {0: "scores", 1: "factor u", 2: "reconstruct-apply", 3: "csr densify"}
 
 
 def cpu_baseline(wl, budget_s):
@@ -144,18 +143,37 @@ def main():
     ctx.reset_timing()
     del big
 
-    flops = 2.0 * wl.N * wl.J * wl.D                        # per launch, scores and reconstruction alike
-    dom = max((f for f in per_kernel if f in (0, 2)), key=lambda f: per_kernel[f][1])
+    # Roofline of the dominant contraction.  fp32 workloads: both contractions are bound by the
+    # fp32 matrix cores (2*N*J*D flops per launch).  bf16 workload: both are bound by streaming W
+    # through HBM; the algorithmic bytes per launch are W once (scores) / twice (reconstruct)
+    # plus the factor operands.
+    S = ctx.plan_info()["fwd_split_k"]
+    flops = 2.0 * wl.N * wl.J * wl.D
+    cands = [f for f in per_kernel if f in (0, 2)]
+    if wl.model == "l2svm" and 0 in cands:
+        cands.remove(0)                                     # CSR scores: a gather kernel, no dense roofline
+    dom = max(cands, key=lambda f: per_kernel[f][1])
     us = per_kernel[dom][1]
-    achieved = flops / (us * 1e-6) / 1e12
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(f"{args.config}:{dom}")
-    roofline = {"bound": "mfma", "kernel": per_kernel[dom][0], "achieved": achieved,
-                "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                "traffic": traffic, "us_per_launch": us,
-                "kernels_us": {v[0]: round(v[1], 2) for v in per_kernel.values()}}
+    if wl.dtype == "bf16":
+        wbytes = 4.0 * wl.J * wl.D
+        if dom == 0:
+            alg = wbytes + 2.0 * wl.N * wl.D * 2 + S * 4.0 * wl.N * wl.J
+        else:
+            alg = 2.0 * wbytes + 2.0 * wl.N * (wl.J + wl.D)
+        achieved = alg / (us * 1e-6) / 1e9
+        roofline = {"bound": "hbm", "kernel": per_kernel[dom][0], "achieved": achieved, "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "traffic": traffic,
+                    "algorithmic_bytes": alg, "us_per_launch": us}
+    else:
+        achieved = flops / (us * 1e-6) / 1e12
+        roofline = {"bound": "mfma", "kernel": per_kernel[dom][0], "achieved": achieved,
+                    "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                    "traffic": traffic, "algorithmic_flops": flops, "us_per_launch": us}
+    roofline["kernels_us"] = {v[0]: round(v[1], 2) for v in per_kernel.values()}
 
     out = {
         "metric": "sfb_samples_per_sec", "value": wl.N * args.steps / elapsed, "unit": "samples/s",
