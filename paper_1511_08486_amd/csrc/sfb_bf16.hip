@@ -26,29 +26,39 @@ namespace sfb {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBfBM = 256, kBfBN = 128, kBfBK = 32;
+constexpr int kBfBM = 256, kBfBN = 128;
+constexpr int kBfFwdBK = 32, kBfReconBK = 64;   // k per stage: scores / reconstruction
+constexpr int kBfReconWPS = 1;                  // 1: one workgroup per CU with the W tile prefetched (2 measured no faster)
 constexpr int kBfThreads = 256;
 
 __device__ __forceinline__ void lds_dma16_raw(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
 }
 
-// swizzles: a bf16 tile row is 4 items of 16 bytes, an fp32 tile row 8 items
-__device__ __forceinline__ int swz4(int r) { return (r >> 2) & 3; }
-__device__ __forceinline__ int swz8(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+// Swizzle for a tile whose rows are IPR items of 16 bytes: item c of row r is stored at
+// position c ^ swz<IPR>(r).  For every IPR, sixteen consecutive rows read at the same
+// logical item land in sixteen different 16-byte bank groups.
+template <int IPR> __device__ __forceinline__ int swz(int r);
+template <> __device__ __forceinline__ int swz<4>(int r) { return (r >> 2) & 3; }
+template <> __device__ __forceinline__ int swz<8>(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+template <> __device__ __forceinline__ int swz<16>(int r) { return r & 15; }
 
 enum BfEpilogue { kStoreZ = 0, kUpdateW = 1 };
 
 // B_FP32: B rows are fp32 in memory (W in the score pass) and are rounded to bf16 after the
 // LDS read.  NST: stages in the ring.
-template <bool B_FP32, int EPI, int NST>
-__global__ __launch_bounds__(kBfThreads) void nt_bf16_kernel(
+// WPS: wavefronts per SIMD the register budget must allow (2 = two workgroups per compute
+// unit, which then cover each other's prologue, barrier and epilogue stalls; the W tile is
+// not prefetched in that case, there are no registers to hold it).
+template <bool B_FP32, int EPI, int NST, int BK, int WPS>
+__global__ __launch_bounds__(kBfThreads, WPS) void nt_bf16_kernel(
     const bf16_t* __restrict__ A, int64_t lda, const void* __restrict__ Bv, int64_t ldb, float* __restrict__ C,
     int64_t ldc, int64_t cstride, bf16_t* __restrict__ Vout, int64_t ldv, int M, int N, int K, int k_slice,
     int n_mb, int n_nb, int total) {
-    constexpr int BM = kBfBM, BN = kBfBN, BK = kBfBK;
+    constexpr int BM = kBfBM, BN = kBfBN;
     constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
-    constexpr int A_ITEMS = BM * 4, B_ITEMS = BN * (B_FP32 ? 8 : 4);
+    constexpr int IA = BK / 8, IB = B_FP32 ? BK / 4 : BK / 8;      // 16-byte items per tile row
+    constexpr int A_ITEMS = BM * IA, B_ITEMS = BN * IB;
     constexpr int A_LD = A_ITEMS / kBfThreads, B_LD = B_ITEMS / kBfThreads;
     constexpr int A_BYTES = A_ITEMS * 16, STAGE_BYTES = (A_ITEMS + B_ITEMS) * 16;
     constexpr int KSTEPS = BK / 16;
@@ -87,17 +97,16 @@ __global__ __launch_bounds__(kBfThreads) void nt_bf16_kernel(
     const unsigned char* pb[B_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
-        const int s = tid + i * kBfThreads, r = s >> 2, c = (s & 3) ^ swz4(r);
+        const int s = tid + i * kBfThreads, r = s / IA, c = (s % IA) ^ swz<IA>(r);
         pa[i] = A + (int64_t)min(m0 + r, M - 1) * lda + k_begin + 8 * c;
     }
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
         const int s = tid + i * kBfThreads;
+        const int r = s / IB, c = (s % IB) ^ swz<IB>(r);
         if (B_FP32) {
-            const int r = s >> 3, c = (s & 7) ^ swz8(r);
             pb[i] = (const unsigned char*)((const float*)Bv + (int64_t)min(n0 + r, N - 1) * ldb + k_begin + 4 * c);
         } else {
-            const int r = s >> 2, c = (s & 3) ^ swz4(r);
             pb[i] = (const unsigned char*)((const bf16_t*)Bv + (int64_t)min(n0 + r, N - 1) * ldb + k_begin + 8 * c);
         }
     }
@@ -125,26 +134,26 @@ __global__ __launch_bounds__(kBfThreads) void nt_bf16_kernel(
     int a_off[KSTEPS], b_off[KSTEPS];
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) {
-        a_off[s] = 16 * ((2 * s + half) ^ swz4(l32));
-        b_off[s] = B_FP32 ? 16 * ((4 * s + 2 * half) ^ swz8(l32)) : 16 * ((2 * s + half) ^ swz4(l32));
+        a_off[s] = 16 * ((2 * s + half) ^ swz<IA>(l32));
+        b_off[s] = B_FP32 ? 16 * ((4 * s + 2 * half) ^ swz<IB>(l32)) : 16 * ((2 * s + half) ^ swz<IB>(l32));
     }
-    const int sw8 = swz8(l32);
+    const int swb = swz<IB>(l32);
 
     struct Frag { u32x4 a[MT]; u32x4 b[NT]; u32x4 b2[B_FP32 ? NT : 1]; };
     auto read_frag = [&](Frag& f, int st, int s) {
-        const unsigned char* as = bf_lds + st * STAGE_BYTES + (wm * WM + l32) * 64;
-        const unsigned char* bs = bf_lds + st * STAGE_BYTES + A_BYTES + (wn * WN + l32) * (B_FP32 ? 128 : 64);
+        const unsigned char* as = bf_lds + st * STAGE_BYTES + (wm * WM + l32) * (IA * 16);
+        const unsigned char* bs = bf_lds + st * STAGE_BYTES + A_BYTES + (wn * WN + l32) * (IB * 16);
 #pragma unroll
-        for (int i = 0; i < MT; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(as + i * 32 * 64 + a_off[s]);
+        for (int i = 0; i < MT; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(as + i * 32 * (IA * 16) + a_off[s]);
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             if (B_FP32) {
                 // 8 consecutive k of an fp32 row = two 16-byte items (logical 4s+2h and 4s+2h+1)
-                const unsigned char* row = bs + j * 32 * 128;
+                const unsigned char* row = bs + j * 32 * (IB * 16);
                 f.b[j] = *reinterpret_cast<const u32x4*>(row + b_off[s]);
-                f.b2[j] = *reinterpret_cast<const u32x4*>(row + 16 * ((4 * s + 2 * half + 1) ^ sw8));
+                f.b2[j] = *reinterpret_cast<const u32x4*>(row + 16 * ((4 * s + 2 * half + 1) ^ swb));
             } else {
-                f.b[j] = *reinterpret_cast<const u32x4*>(bs + j * 32 * 64 + b_off[s]);
+                f.b[j] = *reinterpret_cast<const u32x4*>(bs + j * 32 * (IB * 16) + b_off[s]);
             }
         }
     };
@@ -191,7 +200,7 @@ __global__ __launch_bounds__(kBfThreads) void nt_bf16_kernel(
     auto copy_v = [&](int chunk, int st) {
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
-            const int s = tid + i * kBfThreads, r = s >> 2, c = (s & 3) ^ swz4(r);
+            const int s = tid + i * kBfThreads, r = s / IA, c = (s % IA) ^ swz<IA>(r);
             const u32x4 v = *reinterpret_cast<const u32x4*>(bf_lds + st * STAGE_BYTES + 16 * s);
             if (m0 + r < M)
                 *reinterpret_cast<u32x4*>(Vout + (int64_t)(m0 + r) * ldv + k_begin + chunk * BK + 8 * c) = v;
@@ -205,8 +214,9 @@ __global__ __launch_bounds__(kBfThreads) void nt_bf16_kernel(
 
     // reconstruction: request the whole W tile now (clamped addresses, no branches); it is
     // consumed in the epilogue, so HBM latency and the tile's read both hide under the MFMAs
-    float wreg[EPI == kUpdateW ? MT : 1][EPI == kUpdateW ? NT : 1][16];
-    if (EPI == kUpdateW) {
+    constexpr bool PREFETCH_W = (EPI == kUpdateW) && (WPS == 1);
+    float wreg[PREFETCH_W ? MT : 1][PREFETCH_W ? NT : 1][16];
+    if (PREFETCH_W) {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -249,11 +259,26 @@ __global__ __launch_bounds__(kBfThreads) void nt_bf16_kernel(
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const int col = n0 + wn * WN + j * 32 + l32;
-            if (EPI == kUpdateW) {
+            if (PREFETCH_W) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
                     if (row < M && col < N) cout[(int64_t)row * ldc + col] = wreg[i][j][e] + acc[i][j][e];
+                }
+            } else if (EPI == kUpdateW) {
+                // read-modify-write of one 32 x 32 block: all 16 loads first (clamped, so no
+                // branch sits between them), then the adds and the guarded stores
+                const int cc = min(col, N - 1);
+                float w[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                    w[e] = cout[(int64_t)min(row, M - 1) * ldc + cc];
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                    if (row < M && col < N) cout[(int64_t)row * ldc + col] = w[e] + acc[i][j][e];
                 }
             } else {
 #pragma unroll
@@ -328,18 +353,18 @@ hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s) 
                        n_jblk, n_dblk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    constexpr int NST = 3;
-    constexpr size_t lds_bytes = (size_t)NST * (kBfBM * 4 + kBfBN * 4) * 16;
+    constexpr int NST = 3, BK = kBfReconBK, WPS = kBfReconWPS;
+    constexpr size_t lds_bytes = (size_t)NST * (kBfBM + kBfBN) * (BK / 8) * 16;
     static bool raised = false;
     if (lds_bytes > 64 * 1024 && !raised) {
-        e = hipFuncSetAttribute((const void*)nt_bf16_kernel<false, kUpdateW, NST>,
+        e = hipFuncSetAttribute((const void*)nt_bf16_kernel<false, kUpdateW, NST, BK, WPS>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         raised = true;
     }
     const int n_mb = (a.J + kBfBM - 1) / kBfBM, n_nb = (a.D + kBfBN - 1) / kBfBN;
     const int total = n_mb * n_nb;
-    hipLaunchKernelGGL((nt_bf16_kernel<false, kUpdateW, NST>), dim3(total), dim3(kBfThreads), lds_bytes, s, UT, ldn,
+    hipLaunchKernelGGL((nt_bf16_kernel<false, kUpdateW, NST, BK, WPS>), dim3(total), dim3(kBfThreads), lds_bytes, s, UT, ldn,
                        (const void*)VT, ldn, a.w, a.ldw, (int64_t)0, (bf16_t*)nullptr, (int64_t)0, a.J, a.D,
                        (int)ldn, (int)ldn, n_mb, n_nb, total);
     return hipGetLastError();
@@ -348,7 +373,7 @@ hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s) 
 bool forward_bf16_ok(const FwdArgs& a) {
     return a.bf16 && !a.diff && ((uintptr_t)a.a % 16) == 0 && (a.lda % 8) == 0 && ((uintptr_t)a.w % 16) == 0 &&
            (a.ldw % 4) == 0 && (a.v == nullptr || (((uintptr_t)a.v % 16) == 0 && (a.ldv % 8) == 0)) &&
-           (a.D % kBfBK) == 0 && a.D >= kBfBK;
+           (a.D % kBfFwdBK) == 0 && a.D >= kBfFwdBK;
 }
 
 FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D) {
@@ -357,7 +382,7 @@ FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D) {
     p.bm = kBfBM;
     p.bn = kBfBN;
     const int64_t tiles = ((n_rows + kBfBM - 1) / kBfBM) * ((J + kBfBN - 1) / kBfBN);
-    const int64_t chunks = D / kBfBK > 0 ? D / kBfBK : 1;
+    const int64_t chunks = D / kBfFwdBK > 0 ? D / kBfFwdBK : 1;
     // One workgroup per compute unit is resident (the stage ring fills the LDS), so the time
     // goes as rounds-of-256 x 1/slices: take the slice count that wastes the fewest rounds,
     // charging a little for every extra partial-sum round trip.
@@ -373,24 +398,24 @@ FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D) {
     const int64_t per = (chunks + s - 1) / s;
     s = (chunks + per - 1) / per;
     p.split_k = (int)s;
-    p.k_slice = (int)(per * kBfBK);
+    p.k_slice = (int)(per * kBfFwdBK);
     p.grid = (int)(tiles * s);
     return p;
 }
 
 hipError_t launch_forward_bf16(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
-    constexpr int NST = 4;
-    constexpr size_t lds_bytes = (size_t)NST * (kBfBM * 4 + kBfBN * 8) * 16;
+    constexpr int NST = 4, BK = kBfFwdBK;
+    constexpr size_t lds_bytes = (size_t)NST * (kBfBM * (BK / 8) + kBfBN * (BK / 4)) * 16;
     static bool raised = false;
     if (lds_bytes > 64 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)nt_bf16_kernel<true, kStoreZ, NST>,
+        hipError_t e = hipFuncSetAttribute((const void*)nt_bf16_kernel<true, kStoreZ, NST, BK, 1>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         raised = true;
     }
     const int n_mb = (a.n_rows + kBfBM - 1) / kBfBM, n_nb = (a.J + kBfBN - 1) / kBfBN;
     const int total = n_mb * n_nb * p.split_k;
-    hipLaunchKernelGGL((nt_bf16_kernel<true, kStoreZ, NST>), dim3(total), dim3(kBfThreads), lds_bytes, s,
+    hipLaunchKernelGGL((nt_bf16_kernel<true, kStoreZ, NST, BK, 1>), dim3(total), dim3(kBfThreads), lds_bytes, s,
                        (const bf16_t*)a.a, a.lda, (const void*)a.w, a.ldw, a.zp, a.ldz, a.zstride, (bf16_t*)a.v,
                        a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_mb, n_nb, total);
     return hipGetLastError();
