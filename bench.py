@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", default="mlr_medium")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="oracle timing budget (0 = skip)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the pool's steps in a HIP graph and time replays (helps launch-bound tiny configs)")
     ap.add_argument("--plan", default="", help="fwd_bm,fwd_bn,split_k,recon_variant[,fwd_dma] override")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -97,12 +99,38 @@ def main():
     U = torch.empty((wl.N, wl.J), dtype=torch.float32, device=dev)
     V = torch.empty((wl.N, wl.D), dtype=vdt, device=dev)
 
-    def run(k):
+    def run_eager(k):
         for t in range(k):
             b, y = pool[t % len(pool)]
             ctx.step(W, b, y, U, V, wl.eta)
 
+    run = run_eager
     run(args.warmup)
+    if args.graph:
+        # one graph = one pass over the batch pool; replays keep the pool cycling as in the eager loop
+        torch.cuda.synchronize()
+        cap = torch.cuda.Stream(device=dev)
+        with torch.cuda.stream(cap):
+            gctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
+            if args.plan:
+                gctx.set_plan(*vals[:5])
+            for b, y in pool:
+                gctx.step(W, b, y, U, V, wl.eta)      # warm-up on the capture stream
+            cap.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=cap):
+            for b, y in pool:
+                gctx.step(W, b, y, U, V, wl.eta)
+
+        def run_graph(k):
+            assert k % len(pool) == 0, "--graph needs steps and warmup to be multiples of the batch pool size"
+            for _ in range(k // len(pool)):
+                graph.replay()
+
+        run = run_graph
+        args.warmup = max(len(pool), args.warmup // len(pool) * len(pool))
+        args.steps = max(len(pool), args.steps // len(pool) * len(pool))
+        run(args.warmup)
     torch.cuda.synchronize()
     W.copy_(W0)
     torch.cuda.synchronize()
@@ -112,12 +140,12 @@ def main():
     elapsed = time.perf_counter() - t0
     assert bool(torch.isfinite(W).all()), "W is not finite after the timed steps"
 
-    # instrumented pass: same launches, HIP events around each one on the library's stream
+    # instrumented pass: same launches (eager), HIP events around each one on the library's stream
     W.copy_(W0)
     ctx.enable_timing(True)
     ctx.reset_timing()
     k2 = min(args.steps, 500)
-    run(k2)
+    run_eager(k2)
     per_kernel = {}
     for fam, name in FAMILIES.items():
         ms, n = ctx.kernel_time_ms(fam)
@@ -183,7 +211,7 @@ def main():
         "dtype": "f32" if wl.dtype == "f32" else "bf16 features, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.model} J={wl.J} D={wl.D} P={wl.P} B={wl.B} eta={wl.eta}",
-                   "plan": ctx.plan_info()},
+                   "plan": ctx.plan_info(), "launch": "hip graph replay" if args.graph else "eager"},
         "roofline": roofline,
         "stream_copy": {"GB/s": copy_gbs, "bytes_per_launch": copy_bytes,
                         "note": "plain float4 copy kernel, 256 MiB read + 256 MiB written per launch"},

@@ -55,6 +55,37 @@ __device__ __forceinline__ f32x4 load4(const bf16_t* __restrict__ row, int64_t c
     return r;
 }
 
+// Four consecutive elements of row `row` starting at column `col`, for any alignment and any
+// shape, without a branch: every element is loaded from an address clamped into the matrix
+// (which must have at least one row and one column) and replaced by 0 if it lies outside.
+// Independent scalar loads: slower per byte than load4's wide path, but all in flight at once.
+__device__ __forceinline__ f32x4 load4_clamped(const float* __restrict__ base, int64_t row, int64_t ld, int64_t nrows,
+                                               int64_t col, int64_t ncols) {
+    const float* p = base + (row < nrows ? row : nrows - 1) * ld;
+    const bool rin = row < nrows;
+    f32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int64_t c = col + e;
+        const float v = p[c < ncols ? c : ncols - 1];
+        r[e] = (rin && c < ncols) ? v : 0.f;
+    }
+    return r;
+}
+__device__ __forceinline__ f32x4 load4_clamped(const bf16_t* __restrict__ base, int64_t row, int64_t ld, int64_t nrows,
+                                               int64_t col, int64_t ncols) {
+    const bf16_t* p = base + (row < nrows ? row : nrows - 1) * ld;
+    const bool rin = row < nrows;
+    f32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int64_t c = col + e;
+        const float v = bf16_to_f32(p[c < ncols ? c : ncols - 1]);
+        r[e] = (rin && c < ncols) ? v : 0.f;
+    }
+    return r;
+}
+
 // Unguarded, aligned 4-element loads for the fast paths (the caller clamps the address
 // into the matrix and discards what it must not use: no branches around memory ops).
 __device__ __forceinline__ f32x4 ldg4(const float* __restrict__ p) { return *reinterpret_cast<const f32x4*>(p); }

@@ -79,10 +79,9 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
                 r.a[i] = ldraw4(A + off);
                 if (DIFF) r.a2[i] = ldraw4(A2 + off);
             } else {
-                const bool in = row < n_rows;
                 // columns at or beyond k_end belong to the next slice: read them as 0
-                r.a[i] = to_raw<TIn>(in ? load4(A + (int64_t)row * lda, col, k_end, vec_a) : zero4);
-                if (DIFF) r.a2[i] = to_raw<TIn>(in ? load4(A2 + (int64_t)row * lda, col, k_end, vec_a) : zero4);
+                r.a[i] = to_raw<TIn>(load4_clamped(A, row, lda, n_rows, col, k_end));
+                if (DIFF) r.a2[i] = to_raw<TIn>(load4_clamped(A2, row, lda, n_rows, col, k_end));
             }
         }
 #pragma unroll
@@ -92,7 +91,7 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
             if (FAST) {
                 r.b[i] = ldg4(W + (int64_t)min(row, J - 1) * ldw + min(col, D - 4));
             } else {
-                r.b[i] = row < J ? load4(W + (int64_t)row * ldw, col, k_end, vec_w) : zero4;
+                r.b[i] = load4_clamped(W, row, ldw, J, col, k_end);
             }
         }
     };

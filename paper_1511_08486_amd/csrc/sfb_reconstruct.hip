@@ -96,7 +96,7 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
             if (FAST) {
                 r.u[i] = ldg4(U + (int64_t)min(k, N - 1) * ldu + min(c, J - 4));
             } else {
-                r.u[i] = k < N ? load4(U + (int64_t)k * ldu, c, J, vec_u) : zero4;
+                r.u[i] = load4_clamped(U, k, ldu, N, c, J);
             }
         }
 #pragma unroll
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
             if (FAST) {
                 r.v[i] = ldraw4(V + (int64_t)min(k, N - 1) * ldv + c);
             } else {
-                r.v[i] = to_raw<TV>(k < N ? load4(V + (int64_t)k * ldv, c, D, vec_v) : zero4);
+                r.v[i] = to_raw<TV>(load4_clamped(V, k, ldv, N, c, D));
             }
         }
     };
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
             if (FAST) {
                 wreg[t][x] = ldg4(W + (int64_t)min(row, J - 1) * ldw + d0 + 4 * l32);
             } else {
-                wreg[t][x] = row < J ? load4(W + (int64_t)row * ldw, d0 + 4 * l32, D, vec_w) : zero4;
+                wreg[t][x] = load4_clamped(W, row, ldw, J, d0 + 4 * l32, D);
             }
         }
     fetch(r1, BK);
@@ -266,8 +266,6 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
         for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int x = 0; x < EH; ++x) {
-                constexpr int dummy = 0;
-                (void)dummy;
                 const int e = K * EH + x;
                 const int m = 8 * (e / 4) + 4 * half + (e % 4);
                 const int row = j0 + wr * WMR + MT * m + t;
@@ -304,7 +302,7 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
 
 // BK factor pairs per stage, NST stages in the ring (NST - 1 of them in flight ahead).
 template <int MT, int NWR, int BK, int NST>
-__global__ __launch_bounds__(NWR * 64) void reconstruct_apply_dma_kernel(
+__global__ __launch_bounds__(NWR * 64, 1) void reconstruct_apply_dma_kernel(
     float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const float* __restrict__ V,
     int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total) {
     constexpr int BN = kReconBN, G = kReconGroup;
@@ -342,14 +340,20 @@ __global__ __launch_bounds__(NWR * 64) void reconstruct_apply_dma_kernel(
     const uint32_t lds0 = (uint32_t)(uintptr_t)recon_lds;
     const int64_t ustep = (int64_t)BK * ldu, vstep = (int64_t)BK * ldv;
 
-    auto issue = [&](int chunk, int st) {
+    // DMA number i (U items first, then V items) of stage `st` for chunk `chunk`
+    auto issue_one = [&](int chunk, int st, int i) {
         const uint32_t ubase =
             __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(st * STAGE_FLOATS + wave * 64 * 4) * 4u);
-        const uint32_t vbase = ubase + (uint32_t)(BK * BM) * 4u;
+        if (i < U_LD) {
+            lds_dma16(pu[i] + chunk * ustep, ubase + (uint32_t)(i * THREADS * 16));
+        } else {
+            const uint32_t vbase = ubase + (uint32_t)(BK * BM) * 4u;
+            lds_dma16(pv[i - U_LD] + chunk * vstep, vbase + (uint32_t)((i - U_LD) * THREADS * 16));
+        }
+    };
+    auto issue = [&](int chunk, int st) {
 #pragma unroll
-        for (int i = 0; i < U_LD; ++i) lds_dma16(pu[i] + chunk * ustep, ubase + (uint32_t)(i * THREADS * 16));
-#pragma unroll
-        for (int i = 0; i < V_LD; ++i) lds_dma16(pv[i] + chunk * vstep, vbase + (uint32_t)(i * THREADS * 16));
+        for (int i = 0; i < U_LD + V_LD; ++i) issue_one(chunk, st, i);
     };
 
     f32x16 acc[MT][4];
@@ -390,14 +394,36 @@ __global__ __launch_bounds__(NWR * 64) void reconstruct_apply_dma_kernel(
                 for (int n = 0; n < 4; ++n)
                     acc[t][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[s][t], f.b[s][n], acc[t][n], 0, 0, 0);
     };
-    auto compute = [&](int st) {
+    // The same MFMAs with one DMA of a later stage slipped in after each of the first
+    // U_LD + V_LD of them: the address arithmetic and the DMA issue run in the shadow of a
+    // 64-cycle MFMA instead of holding up the first MFMA of the stage.
+    auto mma_frag_issue = [&](const Frag& f, int chunk, int st) {
+#pragma unroll
+        for (int s = 0; s < G; ++s)
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int n = 0; n < 4; ++n) {
+                    acc[t][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[s][t], f.b[s][n], acc[t][n], 0, 0, 0);
+                    const int slot = (s * MT + t) * 4 + n;
+                    if (slot < U_LD + V_LD) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        issue_one(chunk, st, slot);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+    };
+    static_assert(U_LD + V_LD <= G * MT * 4, "more DMAs per stage than MFMAs in the first fragment group");
+    // issue_chunk >= 0: the DMAs of that chunk (into stage issue_st) ride along the first group
+    auto compute = [&](int st, int issue_chunk, int issue_st) {
         Frag f0, f1;
         read_frag(f0, st, 0);
 #pragma unroll
         for (int g = 0; g < NGROUPS; g += 2) {
             if (g + 1 < NGROUPS) read_frag(f1, st, g + 1);
             __builtin_amdgcn_sched_barrier(0);
-            mma_frag(f0);
+            if (g == 0 && issue_chunk >= 0) mma_frag_issue(f0, issue_chunk, issue_st);
+            else mma_frag(f0);
             __builtin_amdgcn_sched_barrier(0);
             if (g + 1 < NGROUPS) {
                 if (g + 2 < NGROUPS) read_frag(f0, st, g + 2);
@@ -419,8 +445,7 @@ __global__ __launch_bounds__(NWR * 64) void reconstruct_apply_dma_kernel(
         const int younger = min(n_chunks - 1 - c, NST - 2);   // chunks issued after chunk c
         if (younger >= 1) wait_vmcnt<U_LD + V_LD>(); else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
-        if (c + NST - 1 < n_chunks) issue(c + NST - 1, (st + NST - 1) % NST);
-        compute(st);
+        compute(st, c + NST - 1 < n_chunks ? c + NST - 1 : -1, (st + NST - 1) % NST);
     };
     static_assert(NST == 2 || NST == 3, "ring depth");
     // Chunk 0 first, with nothing else competing for HBM; the W tile is requested right
@@ -499,8 +524,6 @@ static const ReconVariant kReconVariants[] = {
     {2, 2, 2, false},  // 6: 128 x 128, 4 wavefronts of 64 rows
     {1, 4, 1, true},   // 7: 128 x 128, 4 wavefronts, LDS-DMA staging (falls back to 0)
     {1, 2, 1, true},   // 8: 64 x 128, 2 wavefronts, LDS-DMA staging (falls back to 1)
-    {2, 4, 1, true},   // 9: 256 x 128, 4 wavefronts, LDS-DMA staging (falls back to 3)
-    {1, 4, 1, true},   // 10: as 7 with 64-pair stages, two-stage ring (falls back to 0)
 };
 constexpr int kNumReconVariants = sizeof(kReconVariants) / sizeof(kReconVariants[0]);
 
@@ -512,13 +535,19 @@ ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
     // 7 and 8 are the LDS-DMA forms of the 128- and 64-row tiles (they fall back to the
     // register-staged kernel by themselves when the shape does not allow DMA).
     const int order[] = {7, 8, 2};
-    int variant = 2;
+    int variant = -1;
     for (int v : order) {
         const int64_t bm = 32 * kReconVariants[v].mt * kReconVariants[v].nwr;
         const int64_t tiles = ((J + bm - 1) / bm) * ((D + kReconBN - 1) / kReconBN);
         if (tiles >= 256) { variant = v; break; }
     }
-    if (J <= 32) variant = 2;
+    if (variant < 0) {
+        // too small to fill the chip whatever the tile, so latency decides: 64-row tiles give
+        // the most workgroups that still have two wavefronts each; up to 64 rows one 128-row
+        // tile is used for its four wavefronts (more lanes to fetch with; the surplus
+        // wavefronts multiply clamped rows that are never stored)
+        variant = J > 64 ? 8 : 7;
+    }
     return plan_reconstruct_variant(J, D, variant);
 }
 
@@ -580,15 +609,13 @@ static hipError_t launch_recon_v(const ReconArgs& a, const ReconPlan& p, hipStre
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s) {
     ReconPlan q = p;
     if (kReconVariants[p.variant].dma) {
-        if (dma_ok(a, p.variant == 10 ? 64 : kReconBK)) {
+        if (dma_ok(a, kReconBK)) {
             switch (p.variant) {
                 case 7: return launch_recon_dma<1, 4, kReconBK, 3>(a, s);
                 case 8: return launch_recon_dma<1, 2, kReconBK, 3>(a, s);
-                case 9: return launch_recon_dma<2, 4, kReconBK, 3>(a, s);
-                case 10: return launch_recon_dma<1, 4, 64, 2>(a, s);
             }
         }
-        q.variant = p.variant == 8 ? 1 : (p.variant == 9 ? 3 : 0);   // same tile, register staging
+        q.variant = p.variant == 8 ? 1 : 0;   // same tile, register staging
     }
     return a.bf16 ? launch_recon_v<bf16_t>(a, q, s) : launch_recon_v<float>(a, q, s);
 }
