@@ -108,6 +108,29 @@ def test_l2svm_dense_score_fallback_full_size(sfb):
 
 
 @pytest.mark.timeout(900)
+def test_l2svm_batch_with_no_stored_entries(sfb):
+    """nnz = 0: every score is 0, u_j = -2 t_j, V = 0, and W still moves by eta/B * sum u v^T = 0."""
+    wl = workloads.make("l2svm", seed=5, J=40, D=256, P=2, B=8, steps=1, pool=1)
+    b = wl.batch(0)
+    b["col"], b["val"] = b["col"][:0], b["val"][:0]
+    b["rowptr"] = np.zeros(wl.N + 1, dtype=np.int32)
+    for plan in (None, dict(fwd_dma=3)):
+        run_chain(wl, 1, TOL32, plan=plan)
+
+
+@pytest.mark.parametrize("model,J", [("mlr", 13001), ("dml", 12800), ("l2svm", 12290)])
+def test_rows_longer_than_the_register_kernel_covers(sfb, model, J):
+    """J > 12288 takes the three-pass factor kernel."""
+    name = {"mlr": "mlr_tiny", "dml": "dml", "l2svm": "l2svm"}[model]
+    over = dict(J=J, D=64, P=2, B=3, steps=2, pool=1)
+    if model == "l2svm":
+        over["density"] = 0.2
+    wl = workloads.make(name, seed=7, **over)
+    if model == "dml":
+        wl.W0 *= 0.05          # keep |z|^2 well below the hinge kink with 12800 latent dimensions
+    run_chain(wl, 2, TOL32, dml_guard=1e-4)
+
+
 def test_mlr_large_bf16_two_steps(sfb):
     wl = workloads.make("mlr_large", pool=2)
     worst = run_chain(wl, 2, TOLBF)
