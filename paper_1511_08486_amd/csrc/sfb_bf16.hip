@@ -26,10 +26,13 @@ namespace sfb {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBfBM = 256, kBfBN = 128;
-constexpr int kBfFwdBK = 32, kBfReconBK = 64;   // k per stage: scores / reconstruction
-constexpr int kBfReconWPS = 1;                  // 1: one workgroup per CU with the W tile prefetched (2 measured no faster)
-constexpr int kBfThreads = 256;
+// Tile shapes.  Reconstruction: 256 x 128 (rows of W x columns of W), 2 x 2 wavefronts, 64-deep
+// stages, one workgroup per CU with the W tile prefetched (two per CU measured no faster).
+// Scores: 256 samples x 256 classes, 4 x 2 wavefronts (two per SIMD): the feature operand is
+// re-read once per class block, so wide class blocks halve that traffic, and 80 tiles x 3
+// slices of D fill the chip in a single round.
+constexpr int kBfReconBM = 256, kBfReconBN = 128, kBfReconBK = 64, kBfReconWPS = 1;
+constexpr int kBfFwdBM = 256, kBfFwdBN = 256, kBfFwdBK = 32;
 
 __device__ __forceinline__ void lds_dma16_raw(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
@@ -50,13 +53,15 @@ enum BfEpilogue { kStoreZ = 0, kUpdateW = 1 };
 // WPS: wavefronts per SIMD the register budget must allow (2 = two workgroups per compute
 // unit, which then cover each other's prologue, barrier and epilogue stalls; the W tile is
 // not prefetched in that case, there are no registers to hold it).
-template <bool B_FP32, int EPI, int NST, int BK, int WPS>
-__global__ __launch_bounds__(kBfThreads, WPS) void nt_bf16_kernel(
+// BM x BN tile computed by WGM x WGN wavefronts.
+template <bool B_FP32, int EPI, int NST, int BK, int WPS, int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(WGM * WGN * 64, WPS) void nt_bf16_kernel(
     const bf16_t* __restrict__ A, int64_t lda, const void* __restrict__ Bv, int64_t ldb, float* __restrict__ C,
     int64_t ldc, int64_t cstride, bf16_t* __restrict__ Vout, int64_t ldv, int M, int N, int K, int k_slice,
     int n_mb, int n_nb, int total) {
-    constexpr int BM = kBfBM, BN = kBfBN;
-    constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32;
+    constexpr int kBfThreads = WGM * WGN * 64;
+    constexpr int WM = BM / WGM, WN = BN / WGN, MT = WM / 32, NT = WN / 32;
+    static_assert(MT >= 1 && NT >= 1 && MT * 32 * WGM == BM && NT * 32 * WGN == BN, "tile / wavefront grid mismatch");
     constexpr int IA = BK / 8, IB = B_FP32 ? BK / 4 : BK / 8;      // 16-byte items per tile row
     constexpr int A_ITEMS = BM * IA, B_ITEMS = BN * IB;
     constexpr int A_LD = A_ITEMS / kBfThreads, B_LD = B_ITEMS / kBfThreads;
@@ -66,7 +71,7 @@ __global__ __launch_bounds__(kBfThreads, WPS) void nt_bf16_kernel(
     extern __shared__ __attribute__((aligned(16))) unsigned char bf_lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int l32 = lane & 31, half = lane >> 5;
 
     // consecutive ids share the B block (W rows in the score pass: the workgroups that
@@ -354,17 +359,18 @@ hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s) 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     constexpr int NST = 3, BK = kBfReconBK, WPS = kBfReconWPS;
-    constexpr size_t lds_bytes = (size_t)NST * (kBfBM + kBfBN) * (BK / 8) * 16;
+    constexpr int BM = kBfReconBM, BN = kBfReconBN;
+    constexpr size_t lds_bytes = (size_t)NST * (BM + BN) * (BK / 8) * 16;
     static bool raised = false;
     if (lds_bytes > 64 * 1024 && !raised) {
-        e = hipFuncSetAttribute((const void*)nt_bf16_kernel<false, kUpdateW, NST, BK, WPS>,
+        e = hipFuncSetAttribute((const void*)nt_bf16_kernel<false, kUpdateW, NST, BK, WPS, BM, BN, 2, 2>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    const int n_mb = (a.J + kBfBM - 1) / kBfBM, n_nb = (a.D + kBfBN - 1) / kBfBN;
+    const int n_mb = (a.J + BM - 1) / BM, n_nb = (a.D + BN - 1) / BN;
     const int total = n_mb * n_nb;
-    hipLaunchKernelGGL((nt_bf16_kernel<false, kUpdateW, NST, BK, WPS>), dim3(total), dim3(kBfThreads), lds_bytes, s, UT, ldn,
+    hipLaunchKernelGGL((nt_bf16_kernel<false, kUpdateW, NST, BK, WPS, BM, BN, 2, 2>), dim3(total), dim3(256), lds_bytes, s, UT, ldn,
                        (const void*)VT, ldn, a.w, a.ldw, (int64_t)0, (bf16_t*)nullptr, (int64_t)0, a.J, a.D,
                        (int)ldn, (int)ldn, n_mb, n_nb, total);
     return hipGetLastError();
@@ -379,9 +385,9 @@ bool forward_bf16_ok(const FwdArgs& a) {
 FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D) {
     FwdPlan p;
     p.dma = true;
-    p.bm = kBfBM;
-    p.bn = kBfBN;
-    const int64_t tiles = ((n_rows + kBfBM - 1) / kBfBM) * ((J + kBfBN - 1) / kBfBN);
+    p.bm = kBfFwdBM;
+    p.bn = kBfFwdBN;
+    const int64_t tiles = ((n_rows + kBfFwdBM - 1) / kBfFwdBM) * ((J + kBfFwdBN - 1) / kBfFwdBN);
     const int64_t chunks = D / kBfFwdBK > 0 ? D / kBfFwdBK : 1;
     // One workgroup per compute unit is resident (the stage ring fills the LDS), so the time
     // goes as rounds-of-256 x 1/slices: take the slice count that wastes the fewest rounds,
@@ -404,18 +410,18 @@ FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D) {
 }
 
 hipError_t launch_forward_bf16(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
-    constexpr int NST = 4, BK = kBfFwdBK;
-    constexpr size_t lds_bytes = (size_t)NST * (kBfBM * (BK / 8) + kBfBN * (BK / 4)) * 16;
+    constexpr int NST = 3, BK = kBfFwdBK, BM = kBfFwdBM, BN = kBfFwdBN;
+    constexpr size_t lds_bytes = (size_t)NST * (BM * (BK / 8) + BN * (BK / 4)) * 16;
     static bool raised = false;
     if (lds_bytes > 64 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)nt_bf16_kernel<true, kStoreZ, NST, BK, 1>,
+        hipError_t e = hipFuncSetAttribute((const void*)nt_bf16_kernel<true, kStoreZ, NST, BK, 2, BM, BN, 4, 2>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    const int n_mb = (a.n_rows + kBfBM - 1) / kBfBM, n_nb = (a.J + kBfBN - 1) / kBfBN;
+    const int n_mb = (a.n_rows + BM - 1) / BM, n_nb = (a.J + BN - 1) / BN;
     const int total = n_mb * n_nb * p.split_k;
-    hipLaunchKernelGGL((nt_bf16_kernel<true, kStoreZ, NST, BK, 1>), dim3(total), dim3(kBfThreads), lds_bytes, s,
+    hipLaunchKernelGGL((nt_bf16_kernel<true, kStoreZ, NST, BK, 2, BM, BN, 4, 2>), dim3(total), dim3(512), lds_bytes, s,
                        (const bf16_t*)a.a, a.lda, (const void*)a.w, a.ldw, a.zp, a.ldz, a.zstride, (bf16_t*)a.v,
                        a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_mb, n_nb, total);
     return hipGetLastError();
