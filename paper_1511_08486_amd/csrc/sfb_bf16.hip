@@ -26,12 +26,13 @@ namespace sfb {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Tile shapes.  Reconstruction: 256 x 128 (rows of W x columns of W), 2 x 2 wavefronts, 64-deep
-// stages, one workgroup per CU with the W tile prefetched (two per CU measured no faster).
+// Tile shapes.  Reconstruction: 256 x 128 (rows of W x columns of W), 2 x 2 wavefronts, 32-deep
+// stages (72 KB of LDS), two workgroups per compute unit: one multiplies while the other sits
+// in its read-modify-write of W, whose loads and stores are paced by HBM.
 // Scores: 256 samples x 256 classes, 4 x 2 wavefronts (two per SIMD): the feature operand is
 // re-read once per class block, so wide class blocks halve that traffic, and 80 tiles x 3
 // slices of D fill the chip in a single round.
-constexpr int kBfReconBM = 256, kBfReconBN = 128, kBfReconBK = 64, kBfReconWPS = 1;
+constexpr int kBfReconBM = 256, kBfReconBN = 128, kBfReconBK = 32, kBfReconWPS = 2;
 constexpr int kBfFwdBM = 256, kBfFwdBN = 256, kBfFwdBK = 32;
 
 __device__ __forceinline__ void lds_dma16_raw(const void* g, uint32_t lds_addr) {
@@ -50,15 +51,14 @@ enum BfEpilogue { kStoreZ = 0, kUpdateW = 1 };
 
 // B_FP32: B rows are fp32 in memory (W in the score pass) and are rounded to bf16 after the
 // LDS read.  NST: stages in the ring.
-// WPS: wavefronts per SIMD the register budget must allow (2 = two workgroups per compute
-// unit, which then cover each other's prologue, barrier and epilogue stalls; the W tile is
-// not prefetched in that case, there are no registers to hold it).
+// WPS: wavefronts per SIMD the register budget must allow (2 = two workgroups of four
+// wavefronts, or one of eight, per compute unit).
 // BM x BN tile computed by WGM x WGN wavefronts.
 template <bool B_FP32, int EPI, int NST, int BK, int WPS, int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(WGM * WGN * 64, WPS) void nt_bf16_kernel(
     const bf16_t* __restrict__ A, int64_t lda, const void* __restrict__ Bv, int64_t ldb, float* __restrict__ C,
     int64_t ldc, int64_t cstride, bf16_t* __restrict__ Vout, int64_t ldv, int M, int N, int K, int k_slice,
-    int n_mb, int n_nb, int total) {
+    int n_mb, int n_nb, int total, int band) {
     constexpr int kBfThreads = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN, MT = WM / 32, NT = WN / 32;
     static_assert(MT >= 1 && NT >= 1 && MT * 32 * WGM == BM && NT * 32 * WGN == BN, "tile / wavefront grid mismatch");
@@ -79,14 +79,13 @@ __global__ __launch_bounds__(WGM * WGN * 64, WPS) void nt_bf16_kernel(
     int id = xcd_contiguous_id(blockIdx.x, total);
     int mb, nb, ks;
     if (EPI == kUpdateW) {
-        // one slice; walk the tile grid in bands of 8 B-blocks with the A block fastest
-        // inside a band: a band's 8 B-blocks (1 MB) stay in the die's L2 while the A blocks
-        // stream past them once per band
-        constexpr int BAND = 8;
+        // one slice; walk the tile grid in bands of `band` B-blocks with the A block fastest
+        // inside a band: a band's B-blocks stay in the die's L2 (the host sizes the band for
+        // that, ideally one band per die) while the A blocks stream past them once per band
         ks = 0;
-        const int band = id / (BAND * n_mb), rem = id - band * BAND * n_mb;
-        const int width = min(BAND, n_nb - band * BAND);     // the last band may be narrower
-        nb = band * BAND + rem % width;
+        const int bi = id / (band * n_mb), rem = id - bi * band * n_mb;
+        const int width = min(band, n_nb - bi * band);     // the last band may be narrower
+        nb = bi * band + rem % width;
         mb = rem / width;
     } else {
         mb = id % n_mb;
@@ -217,24 +216,6 @@ __global__ __launch_bounds__(WGM * WGN * 64, WPS) void nt_bf16_kernel(
     for (int p = 0; p < NST - 1; ++p)
         if (p < n_chunks) issue(p, p);
 
-    // reconstruction: request the whole W tile now (clamped addresses, no branches); it is
-    // consumed in the epilogue, so HBM latency and the tile's read both hide under the MFMAs
-    constexpr bool PREFETCH_W = (EPI == kUpdateW) && (WPS == 1);
-    float wreg[PREFETCH_W ? MT : 1][PREFETCH_W ? NT : 1][16];
-    if (PREFETCH_W) {
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                const int cc = min(n0 + wn * WN + j * 32 + l32, N - 1);
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                    wreg[i][j][e] = C[(int64_t)min(row, M - 1) * ldc + cc];
-                }
-            }
-        wait_vmcnt<0>();   // these loads are younger than the DMAs above: settle the count once
-    }
     auto step = [&](int c, int st) {
         // younger DMAs that may still be in flight: those of the next NST-2 chunks
         const int younger = min(n_chunks - 1 - c, NST - 2);
@@ -259,38 +240,49 @@ __global__ __launch_bounds__(WGM * WGN * 64, WPS) void nt_bf16_kernel(
     if (NST == 4 && c + 2 < n_chunks) step(c + 2, 2);
 
     float* cout = C + (int64_t)ks * cstride;
+    if (EPI == kUpdateW) {
+        // Read-modify-write of the tile in groups of EG 32 x 32 blocks: all loads of a group
+        // first (addresses clamped into the matrix, so no branch sits between them and 16*EG
+        // loads per lane are in flight), then the adds and the guarded stores.  Each wavefront
+        // instruction covers two full 128-byte lines of W.  The other workgroup resident on
+        // this compute unit multiplies meanwhile.
+        constexpr int EG = 4, NBLK = MT * NT;
+        static_assert(NBLK % EG == 0, "epilogue group");
+#pragma unroll
+        for (int g = 0; g < NBLK; g += EG) {
+            float w[EG][16];
+#pragma unroll
+            for (int b = 0; b < EG; ++b) {
+                const int i = (g + b) / NT, j = (g + b) % NT;
+                const int cc = min(n0 + wn * WN + j * 32 + l32, N - 1);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                    w[b][e] = cout[(int64_t)min(row, M - 1) * ldc + cc];
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < EG; ++b) {
+                const int i = (g + b) / NT, j = (g + b) % NT;
+                const int col = n0 + wn * WN + j * 32 + l32;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                    if (row < M && col < N) cout[(int64_t)row * ldc + col] = w[b][e] + acc[i][j][e];
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const int col = n0 + wn * WN + j * 32 + l32;
-            if (PREFETCH_W) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                    if (row < M && col < N) cout[(int64_t)row * ldc + col] = wreg[i][j][e] + acc[i][j][e];
-                }
-            } else if (EPI == kUpdateW) {
-                // read-modify-write of one 32 x 32 block: all 16 loads first (clamped, so no
-                // branch sits between them), then the adds and the guarded stores
-                const int cc = min(col, N - 1);
-                float w[16];
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                    w[e] = cout[(int64_t)min(row, M - 1) * ldc + cc];
-                }
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                    if (row < M && col < N) cout[(int64_t)row * ldc + col] = w[e] + acc[i][j][e];
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                    if (row < M && col < N) cout[(int64_t)row * ldc + col] = acc[i][j][e];
-                }
+            for (int e = 0; e < 16; ++e) {
+                const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                if (row < M && col < N) cout[(int64_t)row * ldc + col] = acc[i][j][e];
             }
         }
 }
@@ -370,9 +362,14 @@ hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s) 
     }
     const int n_mb = (a.J + BM - 1) / BM, n_nb = (a.D + BN - 1) / BN;
     const int total = n_mb * n_nb;
+    // one band of B-blocks per die if ~3 MB of a 4 MB L2 can hold it, else as many as fit
+    int band = (n_nb + kXcds - 1) / kXcds;
+    const int64_t fit = (3LL << 20) / ((int64_t)BN * ldn * 2);
+    if (band > fit) band = (int)fit;
+    if (band < 1) band = 1;
     hipLaunchKernelGGL((nt_bf16_kernel<false, kUpdateW, NST, BK, WPS, BM, BN, 2, 2>), dim3(total), dim3(256), lds_bytes, s, UT, ldn,
                        (const void*)VT, ldn, a.w, a.ldw, (int64_t)0, (bf16_t*)nullptr, (int64_t)0, a.J, a.D,
-                       (int)ldn, (int)ldn, n_mb, n_nb, total);
+                       (int)ldn, (int)ldn, n_mb, n_nb, total, band);
     return hipGetLastError();
 }
 
@@ -423,7 +420,7 @@ hipError_t launch_forward_bf16(const FwdArgs& a, const FwdPlan& p, hipStream_t s
     const int total = n_mb * n_nb * p.split_k;
     hipLaunchKernelGGL((nt_bf16_kernel<true, kStoreZ, NST, BK, 2, BM, BN, 4, 2>), dim3(total), dim3(512), lds_bytes, s,
                        (const bf16_t*)a.a, a.lda, (const void*)a.w, a.ldw, a.zp, a.ldz, a.zstride, (bf16_t*)a.v,
-                       a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_mb, n_nb, total);
+                       a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_mb, n_nb, total, 1);
     return hipGetLastError();
 }
 
