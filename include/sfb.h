@@ -161,10 +161,12 @@ SFB_API int sfb_last_hip_error(const sfb_ctx *ctx);
 /*
  * Read back the launch plan chosen at creation (for benches and tests): number of split-K
  * slices of the score contraction, and the elapsed-time bookkeeping switch.  When timing is
- * enabled every launch is bracketed by HIP events on the context's stream; sfb_kernel_time_ms
- * synchronises and returns the accumulated milliseconds and launch count of kernel family
- * `which` (0 = scores, 1 = factor u, 2 = reconstruct-apply, 3 = sparse helpers) since the
- * last reset.
+ * enabled the main kernel of every family is launched with a pair of HIP events attached to its
+ * own dispatch (start and stop timestamps of that kernel, nothing else in between; do not
+ * enable it while the stream is being captured into a graph); sfb_kernel_time_ms synchronises
+ * and returns the accumulated milliseconds and launch count of kernel family `which`
+ * (0 = scores, 1 = factor u, 2 = reconstruct-apply: the contraction, without the bf16 path's
+ * operand-packing kernel, 3 = CSR densify / stream copy) since the last reset.
  */
 SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32_t *fwd_grid,
                          int32_t *recon_grid);

@@ -18,6 +18,13 @@ constexpr int kFamilies = 4;  // 0 scores, 1 factor u, 2 reconstruct-apply, 3 sp
 struct EventPair { hipEvent_t a, b; };
 }  // namespace
 
+namespace sfb {
+LaunchEvents& launch_events() {
+    static thread_local LaunchEvents le{nullptr, nullptr, false};
+    return le;
+}
+}  // namespace sfb
+
 struct sfb_ctx {
     sfb_model model;
     int64_t J, D;
@@ -64,7 +71,7 @@ sfb_status hip_fail(sfb_ctx* c, hipError_t e) {
     return SFB_EHIP;
 }
 
-// Brackets one launch with events when timing is on.
+// Arms a pair of events for the next kernel launch when timing is on (see SFB_LAUNCH).
 struct Timed {
     sfb_ctx* c;
     int fam;
@@ -79,12 +86,20 @@ struct Timed {
             on = false;
             return;
         }
-        (void)hipEventRecord(ev.a, c->stream);
+        LaunchEvents& le = launch_events();
+        le.start = ev.a;
+        le.stop = ev.b;
+        le.armed = true;
     }
     ~Timed() {
         if (!on) return;
-        (void)hipEventRecord(ev.b, c->stream);
-        c->used[fam].push_back(ev);
+        LaunchEvents& le = launch_events();
+        if (le.armed) {             // nothing was launched: the events hold no timestamps
+            le.armed = false;
+            c->spare.push_back(ev);
+        } else {
+            c->used[fam].push_back(ev);
+        }
     }
 };
 

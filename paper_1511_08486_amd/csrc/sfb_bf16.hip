@@ -345,6 +345,7 @@ hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s) 
     bf16_t* UT = (bf16_t*)ws;
     bf16_t* VT = (bf16_t*)((char*)ws + up((size_t)a.J * ldn * 2));
     const int n_jblk = (a.J + 63) / 64, n_dblk = (a.D + 63) / 64, n_kblk = (int)(ldn / 64);
+    // plain launch: an armed pair of timing events belongs to the contraction below
     hipLaunchKernelGGL(transpose_pack_kernel, dim3((n_jblk + n_dblk) * n_kblk), dim3(256), 0, s, a.u, a.ldu,
                        (const bf16_t*)a.v, a.ldv, UT, VT, ldn, a.N, a.J, a.D, a.B, a.alpha, a.live_mask, a.use_mask,
                        n_jblk, n_dblk);
@@ -367,7 +368,7 @@ hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s) 
     const int64_t fit = (3LL << 20) / ((int64_t)BN * ldn * 2);
     if (band > fit) band = (int)fit;
     if (band < 1) band = 1;
-    hipLaunchKernelGGL((nt_bf16_kernel<false, kUpdateW, NST, BK, WPS, BM, BN, 2, 2>), dim3(total), dim3(256), lds_bytes, s, UT, ldn,
+    SFB_LAUNCH((nt_bf16_kernel<false, kUpdateW, NST, BK, WPS, BM, BN, 2, 2>), dim3(total), dim3(256), lds_bytes, s, UT, ldn,
                        (const void*)VT, ldn, a.w, a.ldw, (int64_t)0, (bf16_t*)nullptr, (int64_t)0, a.J, a.D,
                        (int)ldn, (int)ldn, n_mb, n_nb, total, band);
     return hipGetLastError();
@@ -418,7 +419,7 @@ hipError_t launch_forward_bf16(const FwdArgs& a, const FwdPlan& p, hipStream_t s
     }
     const int n_mb = (a.n_rows + BM - 1) / BM, n_nb = (a.J + BN - 1) / BN;
     const int total = n_mb * n_nb * p.split_k;
-    hipLaunchKernelGGL((nt_bf16_kernel<true, kStoreZ, NST, BK, 2, BM, BN, 4, 2>), dim3(total), dim3(512), lds_bytes, s,
+    SFB_LAUNCH((nt_bf16_kernel<true, kStoreZ, NST, BK, 2, BM, BN, 4, 2>), dim3(total), dim3(512), lds_bytes, s,
                        (const bf16_t*)a.a, a.lda, (const void*)a.w, a.ldw, a.zp, a.ldz, a.zstride, (bf16_t*)a.v,
                        a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_mb, n_nb, total, 1);
     return hipGetLastError();

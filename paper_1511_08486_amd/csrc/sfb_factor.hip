@@ -202,7 +202,7 @@ template <int MODEL>
 static hipError_t launch_factor_m(const FactorArgs& a, hipStream_t s) {
     const bool vec_u = ((uintptr_t)a.u % 16) == 0 && (a.ldu % 4) == 0;
 #define SFB_FACTOR_LAUNCH(GROUP, R)                                                                     \
-    hipLaunchKernelGGL((factor_u_kernel<MODEL, GROUP, R>),                                              \
+    SFB_LAUNCH((factor_u_kernel<MODEL, GROUP, R>),                                              \
                        dim3((a.n_rows + (kFactorThreads / GROUP) - 1) / (kFactorThreads / GROUP)),      \
                        dim3(kFactorThreads), 0, s, a.zp, a.ldz, a.zstride, a.split_k, a.y, a.u, a.ldu,  \
                        a.loss, a.n_rows, a.J, vec_u)
@@ -211,7 +211,7 @@ static hipError_t launch_factor_m(const FactorArgs& a, hipStream_t s) {
     else if (a.J <= 256 * 4 * 4) SFB_FACTOR_LAUNCH(256, 4);
     else if (a.J <= 256 * 4 * 12) SFB_FACTOR_LAUNCH(256, 12);
     else
-        hipLaunchKernelGGL((factor_u_long_kernel<MODEL>), dim3(a.n_rows), dim3(kFactorThreads), 0, s, a.zp,
+        SFB_LAUNCH((factor_u_long_kernel<MODEL>), dim3(a.n_rows), dim3(kFactorThreads), 0, s, a.zp,
                            a.ldz, a.zstride, a.split_k, a.y, a.u, a.ldu, a.loss, a.n_rows, a.J);
 #undef SFB_FACTOR_LAUNCH
     return hipGetLastError();

@@ -392,7 +392,7 @@ static hipError_t launch_fwd_dma(const FwdArgs& a, const FwdPlan& p, hipStream_t
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((fwd_scores_dma_kernel<BM, BN, DIFF>), dim3(total), dim3(kFwdThreads), lds_bytes, s,
+    SFB_LAUNCH((fwd_scores_dma_kernel<BM, BN, DIFF>), dim3(total), dim3(kFwdThreads), lds_bytes, s,
                        (const float*)a.a, (const float*)a.a2, a.lda, a.w, a.ldw, a.zp, a.ldz, a.zstride, (float*)a.v, a.ldv, a.n_rows,
                        a.J, a.D, p.k_slice, n_nb, n_jb, total);
     return hipGetLastError();
@@ -461,7 +461,7 @@ static hipError_t launch_fwd_f(const FwdArgs& a, const FwdPlan& p, hipStream_t s
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((fwd_scores_kernel<BM, BN, TIn, DIFF, FAST>), dim3(total), dim3(kFwdThreads), lds_bytes,
+    SFB_LAUNCH((fwd_scores_kernel<BM, BN, TIn, DIFF, FAST>), dim3(total), dim3(kFwdThreads), lds_bytes,
                        s, (const TIn*)a.a, (const TIn*)a.a2, a.lda, a.w, a.ldw, a.zp, a.ldz, a.zstride,
                        (TIn*)a.v, a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_nb, n_jb, total, vec_a, vec_w, vec_v);
     return hipGetLastError();

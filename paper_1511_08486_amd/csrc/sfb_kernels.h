@@ -3,11 +3,33 @@
 // already checked shapes and pointers.  Each returns the hipError_t of the launch.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace sfb {
 
 enum Model { kMLR = 0, kDML = 1, kL2SVM = 2 };
+
+// Timing hook.  When a pair of events is armed on the calling thread, the next kernel launched
+// through SFB_LAUNCH carries them: they take the start and stop timestamps of that dispatch
+// itself, so what they measure is the kernel's duration with no stream packets in between.
+struct LaunchEvents {
+    hipEvent_t start, stop;
+    bool armed;
+};
+LaunchEvents& launch_events();
+
+#define SFB_LAUNCH(kernel, grid, block, lds, stream, ...)                                                  \
+    do {                                                                                                    \
+        ::sfb::LaunchEvents& sfb_le_ = ::sfb::launch_events();                                              \
+        if (sfb_le_.armed) {                                                                                \
+            sfb_le_.armed = false;                                                                          \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, sfb_le_.start, sfb_le_.stop, 0,         \
+                                  __VA_ARGS__);                                                             \
+        } else {                                                                                            \
+            hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                              \
+        }                                                                                                   \
+    } while (0)
 
 struct FwdPlan {
     int bm, bn;      // output tile: samples x classes

@@ -501,7 +501,7 @@ static hipError_t launch_recon_dma(const ReconArgs& a, hipStream_t s) {
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((reconstruct_apply_dma_kernel<MT, NWR, BK, NST>), dim3(total), dim3(NWR * 64), lds_bytes, s, a.w,
+    SFB_LAUNCH((reconstruct_apply_dma_kernel<MT, NWR, BK, NST>), dim3(total), dim3(NWR * 64), lds_bytes, s, a.w,
                        a.ldw, a.u, a.ldu, (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total);
     return hipGetLastError();
 }
@@ -573,7 +573,7 @@ static hipError_t launch_recon_f(const ReconArgs& a, hipStream_t s, bool vec_w, 
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((reconstruct_apply_kernel<MT, NWR, KS, TV, FAST, MASK>), dim3(total),
+    SFB_LAUNCH((reconstruct_apply_kernel<MT, NWR, KS, TV, FAST, MASK>), dim3(total),
                        dim3(NWR * KS * 64), lds_bytes, s, a.w, a.ldw, a.u, a.ldu, (const TV*)a.v, a.ldv, a.J, a.D,
                        a.N, a.B, a.alpha, a.live_mask, n_jb, total, vec_w, vec_u, vec_v);
     return hipGetLastError();

@@ -30,7 +30,7 @@ __global__ __launch_bounds__(kDensifyThreads) void csr_densify_kernel(
 
 hipError_t launch_csr_densify(const DensifyArgs& a, hipStream_t s) {
     const bool vec_v = ((uintptr_t)a.v % 16) == 0 && (a.ldv % 4) == 0;
-    hipLaunchKernelGGL(csr_densify_kernel, dim3(a.n_rows), dim3(kDensifyThreads), 0, s, a.rowptr, a.col,
+    SFB_LAUNCH(csr_densify_kernel, dim3(a.n_rows), dim3(kDensifyThreads), 0, s, a.rowptr, a.col,
                        a.val, a.v, a.ldv, a.D, a.nnz, vec_v);
     return hipGetLastError();
 }
@@ -52,7 +52,7 @@ hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStre
     int64_t blocks = (n16 + 255) / 256;
     if (blocks > 256 * 16) blocks = 256 * 16;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const f32x4*)src, (f32x4*)dst,
+    SFB_LAUNCH(stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const f32x4*)src, (f32x4*)dst,
                        n16);
     return hipGetLastError();
 }
@@ -191,7 +191,7 @@ hipError_t launch_csr_scores(const DensifyArgs& a, const float* W, int64_t ldw, 
         raised = lds_bytes;
     }
     const bool vec_w = ((uintptr_t)W % 16) == 0 && (ldw % 4) == 0;
-    hipLaunchKernelGGL(csr_scores_kernel, dim3((J + kSpRows - 1) / kSpRows), dim3(kSpThreads), lds_bytes, s,
+    SFB_LAUNCH(csr_scores_kernel, dim3((J + kSpRows - 1) / kSpRows), dim3(kSpThreads), lds_bytes, s,
                        a.rowptr, a.col, a.val, a.nnz, W, ldw, Z, ldz, a.n_rows, J, a.D, vec_w);
     return hipGetLastError();
 }
