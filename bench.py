@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="record the pool's steps in a HIP graph and time replays (helps launch-bound tiny configs)")
     ap.add_argument("--plan", default="", help="fwd_bm,fwd_bn,split_k,recon_variant[,fwd_dma] override")
+    ap.add_argument("--objective-every", type=int, default=0,
+                    help="after the timed run, replay the steps from W0 (untimed) and report the mean per-sample "
+                         "loss of the batch of every K-th step against samples processed")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -216,6 +219,18 @@ def main():
         "stream_copy": {"GB/s": copy_gbs, "bytes_per_launch": copy_bytes,
                         "note": "plain float4 copy kernel, 256 MiB read + 256 MiB written per launch"},
     }
+    if args.objective_every > 0:
+        # objective vs samples on the synthetic data (Section 6's third panel), from the loss the factor kernel emits
+        W.copy_(W0)
+        loss = torch.empty((wl.N,), dtype=torch.float32, device=dev)
+        curve = []
+        for t in range(args.steps):
+            b, y = pool[t % len(pool)]
+            ctx.step(W, b, y, U, V, wl.eta, loss=loss)
+            if t % args.objective_every == 0 or t == args.steps - 1:
+                curve.append([wl.N * t, float(loss.double().mean().item())])
+        out["objective_curve"] = {"unit": "mean per-sample loss of the step's batch, before its update",
+                                  "samples_vs_loss": curve}
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
     print(json.dumps(out))
