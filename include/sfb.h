@@ -144,11 +144,26 @@ SFB_API sfb_status sfb_reconstruct_apply(sfb_ctx *ctx, float *W, int64_t ldw, co
                                  const void *V, int64_t ldv, float eta, float scale,
                                  const uint8_t *active);
 
+/*
+ * One worker's factors only: W <- W - eta * scale * sum_i u_{p,i} v_{p,i}^T over rows
+ * [p*B, (p+1)*B) of U and V (base pointers of the full N-row buffers) -- what a replica does
+ * when the sufficient factors of worker p arrive (Section 3; Section 4.1: under the
+ * asynchronous and stale-synchronous models arrivals are applied one sender at a time).
+ * Costs a contraction over B rows, not over N.
+ */
+SFB_API sfb_status sfb_reconstruct_apply_worker(sfb_ctx *ctx, float *W, int64_t ldw, const float *U,
+                                        int64_t ldu, const void *V, int64_t ldv, int32_t p, float eta,
+                                        float scale);
+
 /* sfb_compute_factors followed by sfb_reconstruct_apply with scale = 1/B: one full BSP
  * iteration.  U, V (and loss) hold the step's factors afterwards. */
 SFB_API sfb_status sfb_step(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_batch *batch, const int32_t *y,
                     float *U, int64_t ldu, void *V, int64_t ldv, float *loss, float eta,
                     const uint8_t *active);
+
+/* What the context was created with; any pointer may be NULL. */
+SFB_API sfb_status sfb_shape(const sfb_ctx *ctx, int64_t *J, int64_t *D, int32_t *P, int32_t *B,
+                     int32_t *input_dtype);
 
 /* hipStreamSynchronize on the context's stream; SFB_EHIP if the stream reports an error. */
 SFB_API sfb_status sfb_sync(sfb_ctx *ctx);
@@ -189,6 +204,47 @@ SFB_API sfb_status sfb_stream_copy(sfb_ctx *ctx, void *dst, const void *src, siz
 SFB_API sfb_status sfb_enable_timing(sfb_ctx *ctx, int enable);
 SFB_API sfb_status sfb_kernel_time_ms(sfb_ctx *ctx, int which, double *ms, int64_t *launches);
 SFB_API sfb_status sfb_reset_timing(sfb_ctx *ctx);
+
+/*
+ * Stale-synchronous SFB (Section 4.1, "SSP-SFB"; local update rule of Section 5) simulated on
+ * one device: P replicas of W, one per worker, that the caller owns and initialises to the
+ * same W^0.  The caller drives the schedule (who computes, what arrives where and when);
+ * this object keeps the clocks, enforces the two rules and runs the kernels:
+ *   t_p        iterations worker p has completed;
+ *   tau[p][q]  how many of worker q's factor sets replica p has applied (tau[p][p] = t_p: a
+ *              worker applies its own factors at once);
+ *   staleness  worker p may start its next iteration only while t_p - tau[p][q] <= staleness
+ *              for every q; otherwise it pauses (staleness 0 = bulk-synchronous);
+ *   no fast-forward  tau[p][q] <= t_p: a replica never applies more of q's iterations than it
+ *              has completed itself (the condition tau_p^q(c) <= c - 1 of Section 5).
+ * Worker q's factors of iteration t live in rows [q*B, (q+1)*B) of slot t % ring_slots of the
+ * ring buffers until every replica has applied them; ring_slots >= 2*staleness + 2 (the two
+ * rules bound t_q - tau[p][q] by 2*staleness + 2: q is at most staleness + 1 ahead of p, and p
+ * at most staleness + 1 ahead of what it has applied of q).  Each set is applied with the eta of the
+ * iteration that produced it and scale 1/B.
+ *   W_replicas  HOST array of P DEVICE pointers, each [J][ldw] fp32.
+ *   U_ring      DEVICE [ring_slots][N][ldu] fp32;  V_ring  DEVICE [ring_slots][N][ldv] in the
+ *               context's dtype.  The ctx must outlive the simulator; its workspace must be set.
+ */
+typedef struct sfb_ssp sfb_ssp;
+SFB_API sfb_status sfb_ssp_create(sfb_ssp **out, sfb_ctx *ctx, int32_t staleness, float *const *W_replicas,
+                          int64_t ldw, float *U_ring, int64_t ldu, void *V_ring, int64_t ldv,
+                          int32_t ring_slots);
+SFB_API void sfb_ssp_destroy(sfb_ssp *ssp);
+/* Worker p's next iteration on its own B samples (as in sfb_compute_factors_worker), at its
+ * own replica: factors into the ring, own update applied, t_p += 1.  If the staleness rule
+ * forbids it, *blocked = 1 and nothing else happens (SFB_OK); else *blocked = 0.
+ * loss: base of a DEVICE [N] fp32 array of which rows [p*B, (p+1)*B) are written, or NULL.
+ * SFB_EUNSUPPORTED if the ring slot of this iteration still holds a set some replica has not
+ * applied (cannot happen with ring_slots >= 2*staleness + 2). */
+SFB_API sfb_status sfb_ssp_worker_step(sfb_ssp *ssp, int32_t p, const sfb_batch *batch_p, const int32_t *y_p,
+                               float eta, float *loss, int32_t *blocked);
+/* Replica p receives and applies the next `count` factor sets of worker q, oldest first.
+ * SFB_EINVAL (nothing applied) if p == q, or q has not produced that many, or it would break
+ * the no-fast-forward rule. */
+SFB_API sfb_status sfb_ssp_deliver(sfb_ssp *ssp, int32_t p, int32_t q, int32_t count);
+/* Clocks: t [P] and tau [P][P] (row p = replica p), HOST int32 arrays; either may be NULL. */
+SFB_API sfb_status sfb_ssp_state(const sfb_ssp *ssp, int32_t *t, int32_t *tau);
 
 #ifdef __cplusplus
 }

@@ -5,3 +5,4 @@ import this package; it exists so that tests, the smoke check and the
 bench's cpu_baseline leg have an independent definition to compare with.
 """
 from .sfb_oracle import *  # noqa: F401,F403
+from .ssp_oracle import SspOracle  # noqa: F401

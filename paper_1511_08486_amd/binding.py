@@ -10,6 +10,7 @@ import torch
 
 SFB_MLR, SFB_DML, SFB_L2SVM = 0, 1, 2
 SFB_F32, SFB_BF16 = 0, 1
+SFB_EINVAL = -1
 _MODELS = {"mlr": SFB_MLR, "dml": SFB_DML, "l2svm": SFB_L2SVM}
 _DTYPES = {"f32": SFB_F32, "bf16": SFB_BF16}
 
@@ -55,6 +56,13 @@ def _load():
         "sfb_enable_timing": (C.c_int, [vp, C.c_int]),
         "sfb_kernel_time_ms": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
         "sfb_reset_timing": (C.c_int, [vp]),
+        "sfb_reconstruct_apply_worker": (C.c_int, [vp, vp, i64, vp, i64, vp, i64, i32, f32, f32]),
+        "sfb_shape": (C.c_int, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
+        "sfb_ssp_create": (C.c_int, [C.POINTER(vp), vp, i32, C.POINTER(vp), i64, vp, i64, vp, i64, i32]),
+        "sfb_ssp_destroy": (None, [vp]),
+        "sfb_ssp_worker_step": (C.c_int, [vp, i32, pb, vp, f32, vp, C.POINTER(i32)]),
+        "sfb_ssp_deliver": (C.c_int, [vp, i32, i32, i32]),
+        "sfb_ssp_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)          # AttributeError here = the library lacks a declared symbol
@@ -180,6 +188,13 @@ class Sfb:
                                               V.data_ptr(), V.stride(0), float(eta), float(scale), ptr),
                     "sfb_reconstruct_apply")
 
+    def reconstruct_apply_worker(self, W, U, V, p, eta, scale=None):
+        if scale is None:
+            scale = 1.0 / self.B
+        self._check(lib.sfb_reconstruct_apply_worker(self._ctx, W.data_ptr(), W.stride(0), U.data_ptr(), U.stride(0),
+                                                     V.data_ptr(), V.stride(0), int(p), float(eta), float(scale)),
+                    "sfb_reconstruct_apply_worker")
+
     def step(self, W, batch, y, U, V, eta, loss=None, active=None):
         if active is not None and len(active) != self.P:
             raise ValueError("active mask must have P entries")
@@ -217,3 +232,57 @@ class Sfb:
 
     def reset_timing(self):
         self._check(lib.sfb_reset_timing(self._ctx), "sfb_reset_timing")
+
+
+class SspSimulator:
+    """Stale-synchronous SFB on one device: owns P replicas of W and the ring of factor sets,
+    forwards every event to the sfb_ssp_* entry points (which keep the clocks and the rules)."""
+
+    def __init__(self, ctx, W0, staleness, ring_slots=None):
+        self.ctx, self.s = ctx, int(staleness)
+        self.slots = int(ring_slots) if ring_slots is not None else 2 * self.s + 2
+        dev = ctx.device
+        vdt = torch.bfloat16 if ctx.dtype == SFB_BF16 else torch.float32
+        N = ctx.P * ctx.B
+        self.W = [W0.to(dev).clone() for _ in range(ctx.P)]
+        self.U_ring = torch.zeros((self.slots, N, ctx.J), dtype=torch.float32, device=dev)
+        self.V_ring = torch.zeros((self.slots, N, ctx.D), dtype=vdt, device=dev)
+        ptrs = (C.c_void_p * ctx.P)(*[w.data_ptr() for w in self.W])
+        self._ssp = C.c_void_p()
+        ctx._check(lib.sfb_ssp_create(C.byref(self._ssp), ctx._ctx, self.s, ptrs, self.W[0].stride(0),
+                                      self.U_ring.data_ptr(), self.U_ring.stride(1), self.V_ring.data_ptr(),
+                                      self.V_ring.stride(1), self.slots), "sfb_ssp_create")
+
+    def worker_step(self, p, batch_p, y_p, eta, loss=None):
+        """True if worker p ran its next iteration, False if the staleness rule made it pause."""
+        b = batch_p.c_struct()
+        blocked = C.c_int32(0)
+        self.ctx._check(lib.sfb_ssp_worker_step(self._ssp, int(p), C.byref(b), y_p.data_ptr(), float(eta),
+                                                _ptr(loss), C.byref(blocked)), "sfb_ssp_worker_step")
+        return blocked.value == 0
+
+    def deliver(self, p, q, count=1):
+        """True if replica p applied the next `count` factor sets of worker q, False if refused."""
+        status = lib.sfb_ssp_deliver(self._ssp, int(p), int(q), int(count))
+        if status == SFB_EINVAL:
+            return False
+        self.ctx._check(status, "sfb_ssp_deliver")
+        return True
+
+    def state(self):
+        P = self.ctx.P
+        t = (C.c_int32 * P)()
+        tau = (C.c_int32 * (P * P))()
+        self.ctx._check(lib.sfb_ssp_state(self._ssp, t, tau), "sfb_ssp_state")
+        return list(t), [list(tau[p * P:(p + 1) * P]) for p in range(P)]
+
+    def close(self):
+        if getattr(self, "_ssp", None):
+            lib.sfb_ssp_destroy(self._ssp)
+            self._ssp = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

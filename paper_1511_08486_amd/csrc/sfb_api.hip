@@ -187,11 +187,12 @@ sfb_status check_recon(const sfb_ctx* c, float eta, float scale, const uint8_t* 
     return SFB_OK;
 }
 
+// n_rows: factor pairs to contract over (0 = all P*B; a single worker's B otherwise, no mask)
 sfb_status recon_launch(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64_t ldu, const void* V,
-                        int64_t ldv, float eta, float scale, const uint8_t* active) {
+                        int64_t ldv, float eta, float scale, const uint8_t* active, int n_rows = 0) {
     ReconArgs r{};
     r.w = W; r.ldw = ldw; r.u = U; r.ldu = ldu; r.v = V; r.ldv = ldv;
-    r.J = (int)c->J; r.D = (int)c->D; r.N = c->P * c->B; r.B = c->B;
+    r.J = (int)c->J; r.D = (int)c->D; r.N = n_rows > 0 ? n_rows : c->P * c->B; r.B = c->B;
     r.alpha = -eta * scale;
     r.bf16 = c->dtype == SFB_BF16;
     r.use_mask = false;
@@ -295,6 +296,18 @@ sfb_status sfb_reconstruct_apply(sfb_ctx* c, float* W, int64_t ldw, const float*
     return recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active);
 }
 
+sfb_status sfb_reconstruct_apply_worker(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64_t ldu,
+                                        const void* V, int64_t ldv, int32_t p, float eta, float scale) {
+    sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
+    if (s != SFB_OK) return s;
+    s = check_recon(c, eta, scale, nullptr);
+    if (s != SFB_OK) return s;
+    if (p < 0 || p >= c->P) return SFB_ESHAPE;
+    const size_t vsz = c->dtype == SFB_BF16 ? 2 : 4;
+    return recon_launch(c, W, ldw, U + (int64_t)p * c->B * ldu, ldu,
+                        (const char*)V + (size_t)p * c->B * (size_t)ldv * vsz, ldv, eta, scale, nullptr, c->B);
+}
+
 sfb_status sfb_step(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, const int32_t* y, float* U,
                     int64_t ldu, void* V, int64_t ldv, float* loss, float eta, const uint8_t* active) {
     sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
@@ -307,6 +320,16 @@ sfb_status sfb_step(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, c
     s = factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss);
     if (s != SFB_OK) return s;
     return recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active);
+}
+
+sfb_status sfb_shape(const sfb_ctx* c, int64_t* J, int64_t* D, int32_t* P, int32_t* B, int32_t* input_dtype) {
+    if (!c) return SFB_EINVAL;
+    if (J) *J = c->J;
+    if (D) *D = c->D;
+    if (P) *P = c->P;
+    if (B) *B = c->B;
+    if (input_dtype) *input_dtype = (int32_t)c->dtype;
+    return SFB_OK;
 }
 
 sfb_status sfb_sync(sfb_ctx* c) {

@@ -1,0 +1,144 @@
+"""GPU parity of stale-synchronous SFB (sfb_ssp_* through the C ABI) against the fp64 SSP
+oracle: the same seeded list of proposed events is replayed on both sides; which proposals are
+accepted and the clocks must agree exactly, every replica of W within the parity tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from gpu_util import assert_close, to_device
+from oracle.ssp_oracle import SspOracle
+
+pytestmark = pytest.mark.gpu
+
+TOL32 = 1e-4
+TOLBF = 2e-2
+
+
+@pytest.fixture(scope="module")
+def sfb():
+    import paper_1511_08486_amd as m
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return m
+
+
+def device_share(sfb, wl, batch, p, dev):
+    """Worker p's B samples on the device."""
+    share = workloads.worker_share(wl.model, batch, p, wl.B)
+    one = workloads.Workload(name=wl.name, model=wl.model, J=wl.J, D=wl.D, P=1, B=wl.B, eta=wl.eta, steps=1,
+                             dtype=wl.dtype, W0=wl.W0, batches=[share])
+    return share, to_device(one, share, dev)
+
+
+def replay_both(sfb, wl, s, events, max_iter, tol, check_every=8):
+    dev = "cuda:0"
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
+    sim = sfb.SspSimulator(ctx, torch.from_numpy(wl.W0), s)
+    o = SspOracle(wl.model, wl.W0, wl.P, wl.B, s)
+    n_ok = n_refused = 0
+
+    def compare(tag):
+        ctx.sync()
+        t, tau = sim.state()
+        assert t == o.t and tau == o.tau, f"{tag}: clocks differ"
+        for p in range(wl.P):
+            assert_close(sim.W[p].cpu().numpy(), o.replica(p), tol, f"{tag}: replica {p}")
+
+    for k, ev in enumerate(events):
+        if ev[0] == "step":
+            p = ev[1]
+            if o.t[p] >= max_iter:
+                continue
+            share, (db, dy) = device_share(sfb, wl, wl.batch(o.t[p]), p, dev)
+            got = sim.worker_step(p, db, dy, wl.eta)
+            want = o.worker_step(p, share, wl.eta) is not None
+        else:
+            got = sim.deliver(ev[1], ev[2], ev[3])
+            want = o.deliver(ev[1], ev[2], ev[3])
+        assert got == want, f"event {k} {ev}: accepted on the device = {got}, in the oracle = {want}"
+        n_ok += got
+        n_refused += not got
+        if k % check_every == 0:
+            compare(f"event {k} {ev}")
+    compare("end of the proposals")
+    # finish: everybody reaches the same count and receives everything; then every replica is the auxiliary sequence
+    C = max(o.t)
+    for _ in range(50 * C * wl.P * wl.P + 10):
+        moved = False
+        for p in range(wl.P):
+            for q in range(wl.P):
+                if p != q and o.may_deliver(p, q, 1):
+                    assert sim.deliver(p, q, 1) and o.deliver(p, q, 1)
+                    moved = True
+            if o.t[p] < C and o.may_step(p):
+                share, (db, dy) = device_share(sfb, wl, wl.batch(o.t[p]), p, dev)
+                assert sim.worker_step(p, db, dy, wl.eta)
+                assert o.worker_step(p, share, wl.eta) is not None
+                moved = True
+        if not moved:
+            break
+    compare("after the flush")
+    aux = o.auxiliary(C)
+    for p in range(wl.P):
+        assert_close(sim.W[p].cpu().numpy(), aux, tol, f"replica {p} vs the auxiliary sequence")
+    sim.close()
+    ctx.close()
+    return n_ok, n_refused
+
+
+@pytest.mark.parametrize("name,override,s,seed", [
+    ("mlr_tiny", {}, 1, 0),
+    ("mlr_tiny", dict(J=37, D=203, P=3, B=5), 2, 1),
+    ("mlr_tiny", dict(J=130, D=256, P=4, B=32), 3, 2),
+    ("dml", dict(J=24, D=128, P=3, B=16), 1, 3),
+    ("l2svm", dict(J=50, D=256, P=3, B=8, density=0.05), 2, 4),
+])
+def test_random_schedule_matches_the_oracle(sfb, name, override, s, seed):
+    wl = workloads.make(name, seed=seed, **override)
+    ok, refused = replay_both(sfb, wl, s, workloads.ssp_proposals(wl.P, 160, seed=seed), max_iter=8, tol=TOL32)
+    print(f"{name} s={s}: {ok} events accepted, {refused} refused")
+    assert ok > 40 and refused > 5
+
+
+def test_staleness_zero_equals_bsp_step(sfb):
+    """s = 0: each round of P worker steps and all deliveries leaves every replica where sfb_step
+    leaves W (Section 4.1: SSP-SFB with s = 0 is BSP-SFB)."""
+    dev = "cuda:0"
+    wl = workloads.make("mlr_tiny", seed=7, J=64, D=160, P=4, B=32)
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
+    sim = sfb.SspSimulator(ctx, torch.from_numpy(wl.W0), 0)
+    W = torch.from_numpy(wl.W0).to(dev)
+    U = torch.empty((wl.N, wl.J), dtype=torch.float32, device=dev)
+    V = torch.empty((wl.N, wl.D), dtype=torch.float32, device=dev)
+    for r in range(3):
+        b = wl.batch(r)
+        for p in range(wl.P):
+            _, (db, dy) = device_share(sfb, wl, b, p, dev)
+            assert sim.worker_step(p, db, dy, wl.eta)
+        _, (db, dy) = device_share(sfb, wl, b, 0, dev)
+        assert not sim.worker_step(0, db, dy, wl.eta)          # must pause
+        for p in range(wl.P):
+            for q in range(wl.P):
+                if p != q:
+                    assert sim.deliver(p, q, 1)
+        fb, fy = to_device(wl, b, dev)
+        ctx.step(W, fb, fy, U, V, wl.eta)
+        ctx.sync()
+        for p in range(wl.P):
+            assert_close(sim.W[p].cpu().numpy(), W.cpu().numpy().astype(np.float64), 2e-6, f"round {r} replica {p}")
+    sim.close()
+    ctx.close()
+
+
+def test_bf16_replicas(sfb):
+    wl = workloads.make("mlr_large", seed=9, J=96, D=256, P=2, B=64)
+    ok, refused = replay_both(sfb, wl, 1, workloads.ssp_proposals(wl.P, 60, seed=9), max_iter=5, tol=TOLBF)
+    assert ok > 15
+
+
+def test_ring_too_small_is_refused(sfb):
+    wl = workloads.make("mlr_tiny")
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device="cuda:0")
+    with pytest.raises(sfb.SfbError):
+        sfb.SspSimulator(ctx, torch.from_numpy(wl.W0), 2, ring_slots=5)
+    ctx.close()

@@ -156,3 +156,32 @@ def make(name, seed=0, pool=None, **override):
             raise ValueError(model)
     return Workload(name=name, model=model, J=J, D=D, P=P, B=B, eta=cfg["eta"], steps=cfg["steps"],
                     dtype=cfg["dtype"], W0=W0, batches=batches)
+
+
+def worker_share(model, batch, p, B):
+    """Worker p's B samples of a batch (rows [p*B, (p+1)*B)), in the batch's own storage."""
+    rows = slice(p * B, (p + 1) * B)
+    if model == "mlr":
+        return {"A": batch["A"][rows], "y": batch["y"][rows]}
+    if model == "dml":
+        return {"X": batch["X"][rows], "Y": batch["Y"][rows], "y": batch["y"][rows]}
+    rp = batch["rowptr"][p * B:(p + 1) * B + 1]
+    lo, hi = int(rp[0]), int(rp[-1])
+    return {"rowptr": (rp - rp[0]).astype(np.int32), "col": batch["col"][lo:hi], "val": batch["val"][lo:hi],
+            "y": batch["y"][rows], "D": batch["D"]}
+
+
+def ssp_proposals(P, n_events, seed=0, p_step=0.45):
+    """A seeded list of PROPOSED schedule events for a stale-synchronous run: ("step", p) or
+    ("deliver", p, q, count).  No rule of the method is applied here: whoever replays the list
+    decides which proposals are legal and refuses the others."""
+    rng = np.random.default_rng(seed)
+    events = []
+    for _ in range(n_events):
+        if rng.random() < p_step:
+            events.append(("step", int(rng.integers(P))))
+        else:
+            p = int(rng.integers(P))
+            q = int((p + 1 + rng.integers(P - 1)) % P) if P > 1 else p
+            events.append(("deliver", p, q, int(rng.integers(1, 3))))
+    return events
