@@ -108,3 +108,45 @@ def test_strerror_covers_every_status(lib):
     seen = {sfb.sfb_strerror(s) for s in (0, -1, -2, -3, -5, -6, -7)}
     assert len(seen) == 7 and "unknown status" not in seen
     assert sfb.sfb_strerror(-99) == "unknown status"
+
+
+def test_ssp_and_per_sender_calls_validate_before_launching(lib):
+    """Host-side rules of the stale-synchronous scheduler need no GPU: creation checks, a
+    delivery nobody has produced, a worker index out of range."""
+    import paper_1511_08486_amd as sfb
+    ctx = C.c_void_p()
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 8, 16, 3, 4, sfb.SFB_F32, None) == 0
+    J, D, P, B, dt = C.c_int64(), C.c_int64(), C.c_int32(), C.c_int32(), C.c_int32()
+    assert lib.sfb_shape(ctx, C.byref(J), C.byref(D), C.byref(P), C.byref(B), C.byref(dt)) == 0
+    assert (J.value, D.value, P.value, B.value, dt.value) == (8, 16, 3, 4, 0)
+    assert lib.sfb_shape(None, None, None, None, None, None) == -1
+    fake = C.c_void_p(0x1000)
+    assert lib.sfb_reconstruct_apply_worker(ctx, fake, 16, fake, 8, fake, 16, 3, 0.1, 0.25) == -2
+    assert lib.sfb_reconstruct_apply_worker(ctx, fake, 16, fake, 8, fake, 16, -1, 0.1, 0.25) == -2
+    assert lib.sfb_reconstruct_apply_worker(ctx, fake, 16, fake, 8, fake, 16, 0, float("nan"), 0.25) == -1
+    assert lib.sfb_reconstruct_apply_worker(ctx, None, 16, fake, 8, fake, 16, 0, 0.1, 0.25) == -1
+    ssp = C.c_void_p()
+    reps = (C.c_void_p * 3)(0x1000, 0x2000, 0x3000)
+    assert lib.sfb_ssp_create(None, ctx, 1, reps, 16, fake, 8, fake, 16, 4) == -1
+    assert lib.sfb_ssp_create(C.byref(ssp), None, 1, reps, 16, fake, 8, fake, 16, 4) == -1
+    assert lib.sfb_ssp_create(C.byref(ssp), ctx, -1, reps, 16, fake, 8, fake, 16, 4) == -1
+    assert lib.sfb_ssp_create(C.byref(ssp), ctx, 1, reps, 15, fake, 8, fake, 16, 4) == -2       # ldw < D
+    assert lib.sfb_ssp_create(C.byref(ssp), ctx, 1, reps, 16, fake, 8, fake, 16, 3) == -2       # ring < 2s + 2
+    holes = (C.c_void_p * 3)(0x1000, None, 0x3000)
+    assert lib.sfb_ssp_create(C.byref(ssp), ctx, 1, holes, 16, fake, 8, fake, 16, 4) == -1
+    assert not ssp.value
+    assert lib.sfb_ssp_create(C.byref(ssp), ctx, 1, reps, 16, fake, 8, fake, 16, 4) == 0
+    t = (C.c_int32 * 3)()
+    tau = (C.c_int32 * 9)(*([7] * 9))
+    assert lib.sfb_ssp_state(ssp, t, tau) == 0 and list(t) == [0, 0, 0] and list(tau) == [0] * 9
+    assert lib.sfb_ssp_deliver(ssp, 0, 0, 1) == -1          # a worker does not receive from itself
+    assert lib.sfb_ssp_deliver(ssp, 0, 1, 1) == -1          # worker 1 has produced nothing yet
+    assert lib.sfb_ssp_deliver(ssp, 0, 3, 1) == -2
+    assert lib.sfb_ssp_deliver(ssp, 0, 1, 0) == 0           # nothing to apply, nothing launched
+    blocked = C.c_int32(5)
+    assert lib.sfb_ssp_worker_step(ssp, 3, None, None, 0.1, None, C.byref(blocked)) == -2
+    assert lib.sfb_ssp_worker_step(ssp, 0, None, None, 0.1, None, None) == -1
+    assert lib.sfb_ssp_worker_step(ssp, 0, None, fake, 0.1, None, C.byref(blocked)) == -1     # no batch: refused by the factor call
+    assert list(t) == [0, 0, 0]
+    lib.sfb_ssp_destroy(ssp)
+    lib.sfb_destroy(ctx)
