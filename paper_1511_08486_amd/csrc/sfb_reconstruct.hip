@@ -447,11 +447,12 @@ __global__ __launch_bounds__(NWR * 64, 1) void reconstruct_apply_dma_kernel(
         __builtin_amdgcn_s_barrier();
         compute(st, c + NST - 1 < n_chunks ? c + NST - 1 : -1, (st + NST - 1) % NST);
     };
-    static_assert(NST == 2 || NST == 3, "ring depth");
+    static_assert(NST == 3, "ring depth");
     // Chunk 0 first, with nothing else competing for HBM; the W tile is requested right
     // after it (ordinary loads, consumed in the epilogue), so its read overlaps the
     // remaining stages instead of delaying the first MFMA.
     step(0, 0);
+    constexpr int W_LOADS = MT * 16;
     f32x4 wreg[MT][16];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
@@ -461,15 +462,28 @@ __global__ __launch_bounds__(NWR * 64, 1) void reconstruct_apply_dma_kernel(
             const int row = j0 + wave * WMR + MT * m + t;
             wreg[t][e] = ldg4(W + (int64_t)min(row, J - 1) * ldw + d0 + 4 * l32);
         }
+    // The vector-memory counter retires in order and the W loads sit between the DMAs of
+    // chunk 2 (issued during chunk 0) and those of chunk 3: the waits of chunks 1 and 2 count
+    // them among the younger operations, so that neither stalls on the W tile's trip to HBM;
+    // by chunk 3 (two stages later) the tile has long arrived.
+    static_assert(U_LD + V_LD + W_LOADS <= 63, "wait count encoding");
+    auto step_w = [&](int c, int st) {
+        const bool dma_younger = (c == 1) ? (2 < n_chunks) : (3 < n_chunks);
+        if (dma_younger) wait_vmcnt<U_LD + V_LD + W_LOADS>(); else wait_vmcnt<W_LOADS>();
+        __builtin_amdgcn_s_barrier();
+        compute(st, c + NST - 1 < n_chunks ? c + NST - 1 : -1, (st + NST - 1) % NST);
+    };
+    if (1 < n_chunks) step_w(1, 1);
+    if (2 < n_chunks) step_w(2, 2);
 
-    int c = 1;
+    int c = 3;
     for (; c + NST - 1 < n_chunks; c += NST) {
-        step(c, 1 % NST);
-        step(c + 1, 2 % NST);
-        if (NST == 3) step(c + 2, 0);
+        step(c, 0);
+        step(c + 1, 1);
+        step(c + 2, 2);
     }
-    if (c < n_chunks) step(c, 1 % NST);
-    if (NST == 3 && c + 1 < n_chunks) step(c + 1, 2);
+    if (c < n_chunks) step(c, 0);
+    if (c + 1 < n_chunks) step(c + 1, 1);
 
 #pragma unroll
     for (int t = 0; t < MT; ++t)
