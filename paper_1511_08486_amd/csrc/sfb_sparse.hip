@@ -109,69 +109,97 @@ __global__ __launch_bounds__(kSpThreads) void csr_scores_kernel(
     }
     __syncthreads();
 
-    // row pointers of a batch of consecutive samples (clamped into the batch: a row pointer
-    // outside [0, nnz] is a caller error and must not carry an access out of the arrays)
-    auto load_ptrs = [&](int n, int64_t (&p)[kSpBatch + 1]) {
+    // Everything below is 32-bit index arithmetic on purpose (the host checks nnz < 2^31): the
+    // kernel is bound by the number of vector instructions per stored entry, not by memory.
+    const int last = (int)nnz - 1;
+    const uint32_t dmax = (uint32_t)(D - 1);
+    // row pointers of a batch of consecutive samples (clamped into [0, nnz]: a row pointer
+    // outside is a caller error and must not carry an access out of the arrays)
+    auto load_ptrs = [&](int n, int (&p)[kSpBatch + 1]) {
 #pragma unroll
-        for (int s = 0; s <= kSpBatch; ++s) {
-            const int64_t v = rowptr[min(n + s, n_rows)];
-            p[s] = v < 0 ? 0 : (v > nnz ? nnz : v);
-        }
+        for (int s = 0; s <= kSpBatch; ++s) p[s] = min(max(rowptr[min(n + s, n_rows)], 0), last + 1);
     };
-    int64_t ptr[kSpBatch + 1], next_ptr[kSpBatch + 1];
+    int ptr[kSpBatch + 1], next_ptr[kSpBatch + 1];
     int n = wave * kSpBatch;
     if (n < n_rows) load_ptrs(n, ptr);
     for (; n < n_rows; n += NW * kSpBatch) {
         const int n_next = n + NW * kSpBatch;
         if (n_next < n_rows) load_ptrs(n_next, next_ptr);   // one batch ahead
-        // issue every load of the batch's first slabs before using any of them
-        int cc[kSpBatch][kSpPre];
+        // issue every load of the batch's first slabs before using any of them: addresses are
+        // always valid (clamped) and a select zeroes what lies outside the row, so no branch
+        // sits between the loads and all of them are in flight together
+        uint32_t cc[kSpBatch][kSpPre];
         float vv[kSpBatch][kSpPre];
 #pragma unroll
         for (int s = 0; s < kSpBatch; ++s)
 #pragma unroll
             for (int it = 0; it < kSpPre; ++it) {
-                // always a valid address (clamped), the select discards what is out of the row:
-                // no branch sits between the loads, so all of them are in flight together
-                const int64_t e = ptr[s] + it * 64 + lane;
-                const int64_t ec = e < nnz ? e : nnz - 1;
-                const int cl = col[ec];
-                vv[s][it] = val[ec];
-                cc[s][it] = e < ptr[s + 1] ? cl : -1;
+                const int e = ptr[s] + it * 64 + lane;
+                const int ec = min(e, last);
+                const uint32_t cl = (uint32_t)col[ec];
+                const float vl = val[ec];
+                const bool in = e < ptr[s + 1];
+                vv[s][it] = in ? vl : 0.f;
+                cc[s][it] = in ? min(cl, dmax) : 0u;       // a column outside [0, D) is a caller error: stay inside the LDS tile
             }
-        f32x4 acc[kSpBatch];
+        float acc[kSpBatch * kSpRows];                      // [sample][class]
 #pragma unroll
         for (int s = 0; s < kSpBatch; ++s) {
-            acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+            f32x4 a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int it = 0; it < kSpPre; ++it) {
-                const int c = cc[s][it];
-                if (c >= 0 && c < D) acc[s] += vv[s][it] * *reinterpret_cast<const f32x4*>(&wcols[c * 4]);
+            for (int it = 0; it < kSpPre; ++it) a += vv[s][it] * *reinterpret_cast<const f32x4*>(&wcols[cc[s][it] * 4]);
+            // rows longer than the prefetched slabs (uniform trip count per wavefront)
+            for (int e0 = ptr[s] + kSpPre * 64; e0 < ptr[s + 1]; e0 += 64) {
+                const int e = e0 + lane;
+                const int ec = min(e, last);
+                const uint32_t cl = min((uint32_t)col[ec], dmax);
+                const float vl = e < ptr[s + 1] ? val[ec] : 0.f;
+                a += vl * *reinterpret_cast<const f32x4*>(&wcols[cl * 4]);
             }
-            // rows longer than the prefetched slabs
-            for (int64_t e = ptr[s] + kSpPre * 64 + lane; e < ptr[s + 1]; e += 64) {
-                const int c = col[e];
-                const float v = val[e];
-                if (c >= 0 && c < D) acc[s] += v * *reinterpret_cast<const f32x4*>(&wcols[c * 4]);
+#pragma unroll
+            for (int r = 0; r < kSpRows; ++r) acc[s * kSpRows + r] = a[r];
+        }
+        // Halving butterfly over all 16 sums of the batch at once: at every exchange a lane
+        // gives away half of what it still holds and adds what it receives to the other half,
+        // 8 + 4 + 2 + 1 exchanges; then two more for the last factor four.  Lane l ends up with
+        // value index (l >> 2) & 15 summed over all 64 lanes (17 exchanges instead of 96).
+        static_assert(kSpBatch * kSpRows == 16, "butterfly below is written for 16 values");
+        float v8[8], v4[4], v2[2], v1;
+        {
+            const bool hi = lane & 32;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float give = hi ? acc[k] : acc[k + 8], keep = hi ? acc[k + 8] : acc[k];
+                v8[k] = keep + __shfl_xor(give, 32, 64);            // lanes < 32 keep values 0..7, the rest 8..15
             }
         }
-        // halving butterfly per sample: after two exchanges each lane carries one class
+        {
+            const bool hi = lane & 16;
 #pragma unroll
-        for (int s = 0; s < kSpBatch; ++s) {
-            const bool hi = lane & 32;
-            const float g0 = hi ? acc[s].x : acc[s].z, g1 = hi ? acc[s].y : acc[s].w;   // what I give away
-            const float k0 = hi ? acc[s].z : acc[s].x, k1 = hi ? acc[s].w : acc[s].y;   // what I keep
-            const float a0 = k0 + __shfl_xor(g0, 32, 64), a1 = k1 + __shfl_xor(g1, 32, 64);
-            const bool hi2 = lane & 16;
-            const float give = hi2 ? a0 : a1, keep = hi2 ? a1 : a0;
-            float t = keep + __shfl_xor(give, 16, 64);
-            t += __shfl_xor(t, 8, 64);
-            t += __shfl_xor(t, 4, 64);
-            t += __shfl_xor(t, 2, 64);
-            t += __shfl_xor(t, 1, 64);
-            // lanes 0..15 hold class 0, 16..31 class 1, 32..47 class 2, 48..63 class 3
-            const int r = lane >> 4;
-            if ((lane & 15) == 0 && n + s < n_rows && j0 + r < J) Z[(int64_t)(n + s) * ldz + j0 + r] = t;
+            for (int k = 0; k < 4; ++k) {
+                const float give = hi ? v8[k] : v8[k + 4], keep = hi ? v8[k + 4] : v8[k];
+                v4[k] = keep + __shfl_xor(give, 16, 64);
+            }
+        }
+        {
+            const bool hi = lane & 8;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const float give = hi ? v4[k] : v4[k + 2], keep = hi ? v4[k + 2] : v4[k];
+                v2[k] = keep + __shfl_xor(give, 8, 64);
+            }
+        }
+        {
+            const bool hi = lane & 4;
+            const float give = hi ? v2[0] : v2[1], keep = hi ? v2[1] : v2[0];
+            v1 = keep + __shfl_xor(give, 4, 64);
+        }
+        v1 += __shfl_xor(v1, 2, 64);
+        v1 += __shfl_xor(v1, 1, 64);
+        // value index = 8*(lane bit 5) + 4*(bit 4) + 2*(bit 3) + (bit 2) = (lane >> 2) & 15 = sample * 4 + class
+        {
+            const int idx = (lane >> 2) & 15, sm = idx >> 2, r = idx & 3;
+            if ((lane & 3) == 0 && n + sm < n_rows && j0 + r < J) Z[(int64_t)(n + sm) * ldz + j0 + r] = v1;
         }
 #pragma unroll
         for (int s = 0; s <= kSpBatch; ++s) ptr[s] = next_ptr[s];
@@ -179,6 +207,7 @@ __global__ __launch_bounds__(kSpThreads) void csr_scores_kernel(
 }
 
 bool csr_scores_ok(int D) { return (size_t)D * kSpRows * sizeof(float) <= 160 * 1024 - 1024; }
+// (the caller also needs nnz < 2^31: the kernel indexes the CSR arrays with 32-bit integers)
 
 hipError_t launch_csr_scores(const DensifyArgs& a, const float* W, int64_t ldw, float* Z, int64_t ldz, int J,
                              hipStream_t s) {
