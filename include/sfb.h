@@ -192,7 +192,10 @@ SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32
  * 8: 64x128/2 staged by LDS-DMA where the shape allows, else as 0, 1).
  * fwd_dma: bit 0 = stage the score contraction's tiles by LDS-DMA where the shape allows (else
  * always through registers); bit 1 = L2SVM scores by the dense contraction on the densified rows
- * instead of from the CSR entries; < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
+ * instead of from the CSR entries; bit 2 = fp32 scores on the bf16 matrix cores, every fp32 operand split
+ * exactly into three bf16 terms and every product taken as its six leading term products (error
+ * at the level of one fp32 rounding; full batch and 16-byte aligned rows only, else ignored);
+ * < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
  * query sfb_workspace_bytes again.  SFB_EINVAL for a value outside the table. */
 SFB_API sfb_status sfb_set_plan(sfb_ctx *ctx, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k,
                                 int32_t recon_variant, int32_t fwd_dma);

@@ -34,6 +34,8 @@ struct sfb_ctx {
     hipStream_t stream;
     FwdPlan fwd_all, fwd_worker;   // scores of all N rows / of one worker's B rows
     FwdPlan fwd_bf16;              // all N rows on the bf16 matrix cores (bf16 contexts)
+    FwdPlan fwd_split;             // all N rows, fp32 operands split into bf16 terms (64 x 128 tiles)
+    bool split_scores;             // use it where the shape allows
     ReconPlan recon;
     void* ws;
     size_t ws_bytes;
@@ -56,6 +58,10 @@ size_t scores_need(const sfb_ctx* c) {
     if (c->dtype == SFB_BF16) {
         const size_t bf = (size_t)c->fwd_bf16.split_k * (size_t)c->P * c->B * ldz * sizeof(float);
         if (bf > need) need = bf;
+    }
+    if (c->split_scores) {
+        const size_t sp = (size_t)c->fwd_split.split_k * (size_t)c->P * c->B * ldz * sizeof(float);
+        if (sp > need) need = sp;
     }
     return (need + 255) / 256 * 256;
 }
@@ -164,10 +170,14 @@ sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t
     }
     // bf16 features, full batch, aligned: the bf16 matrix-core kernel with its own plan
     const bool on_bf16_cores = bf16 && n_rows == c->P * c->B && n_rows >= 128 && forward_bf16_ok(f);
-    const FwdPlan& used = on_bf16_cores ? c->fwd_bf16 : plan;
+    // fp32 features, full batch, aligned, and the caller opted in: split-bf16 products
+    const bool on_split = !sparse_scores && !bf16 && c->split_scores && n_rows == c->P * c->B && forward_split_ok(f);
+    const FwdPlan& used = on_bf16_cores ? c->fwd_bf16 : on_split ? c->fwd_split : plan;
     if (!sparse_scores) {
         Timed t(c, 0);
-        hipError_t e = on_bf16_cores ? launch_forward_bf16(f, used, c->stream) : launch_forward(f, used, c->stream);
+        hipError_t e = on_bf16_cores ? launch_forward_bf16(f, used, c->stream)
+                       : on_split    ? launch_forward_split(f, used, c->stream)
+                                     : launch_forward(f, used, c->stream);
         if (e != hipSuccess) return hip_fail(c, e);
     }
     FactorArgs g{};
@@ -240,6 +250,20 @@ sfb_status sfb_create(sfb_ctx** out, sfb_model m, int64_t J, int64_t D, int32_t 
     c->fwd_all = plan_forward((int64_t)P * B, J, D);
     c->fwd_worker = plan_forward(B, J, D);
     c->fwd_bf16 = plan_forward_bf16((int64_t)P * B, J, D);
+    {
+        // 64 x 128 tiles; as many slices of D as bring the grid to about two workgroups per compute unit
+        FwdPlan sp{};
+        sp.bm = 64; sp.bn = 128; sp.dma = false;
+        const int64_t tiles = (((int64_t)P * B + 63) / 64) * ((J + 127) / 128);
+        // (two workgroups fit a compute unit and overlap each other's splitting and multiplying)
+        int64_t s = (512 + tiles / 2) / tiles;
+        if (s < 1) s = 1;
+        if (s > 8) s = 8;
+        sp.split_k = (int)s;
+        finish_forward_plan(&sp, (int64_t)P * B, J, D);
+        c->fwd_split = sp;
+    }
+    c->split_scores = false;
     c->recon = plan_reconstruct(J, D, (int64_t)P * B);
     c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->timing = false; c->sparse_forward = true;
     *out = c;
@@ -374,8 +398,9 @@ sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_
     if (fwd_bm > 0) p.bm = fwd_bm;
     if (fwd_bn > 0) p.bn = fwd_bn;
     if (fwd_split_k > 0) p.split_k = fwd_split_k;
-    if (fwd_dma >= 0) p.dma = fwd_dma != 0;
+    if (fwd_dma >= 0) p.dma = (fwd_dma & 1) != 0;
     if (fwd_dma >= 0) c->sparse_forward = (fwd_dma & 2) == 0;   // bit 1 set: dense scores for CSR input
+    if (fwd_dma >= 0) c->split_scores = (fwd_dma & 4) != 0;     // bit 2 set: fp32 scores as split-bf16 products
     finish_forward_plan(&p, (int64_t)c->P * c->B, c->J, c->D);
     c->fwd_all = p;
     if (recon_variant >= 0) c->recon = plan_reconstruct_variant(c->J, c->D, recon_variant);

@@ -59,6 +59,9 @@ struct FwdArgs {
     bool bf16, diff;
 };
 hipError_t launch_forward(const FwdArgs& a, const FwdPlan& p, hipStream_t s);
+// fp32 scores as six bf16 term products per product (sfb_forward_split.hip); 64 x 128 tiles
+bool forward_split_ok(const FwdArgs& a);
+hipError_t launch_forward_split(const FwdArgs& a, const FwdPlan& p, hipStream_t s);
 
 struct FactorArgs {
     const float* zp;      // [split_k][n_rows][ldz]

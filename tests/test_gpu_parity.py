@@ -259,3 +259,42 @@ def test_determinism_same_call_twice_is_bit_identical(sfb):
         res.append((W.clone(), U.clone()))
     assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
     ctx.close()
+
+
+@pytest.mark.parametrize("name,seed,steps,override", [
+    ("mlr_medium", 0, 100, {}),
+    ("dml", 1, 20, {}),
+    ("mlr_tiny", 5, 3, dict(J=130, D=256, P=3, B=40)),      # ragged tiles, one slice of D
+    ("mlr_tiny", 6, 3, dict(J=64, D=96, P=2, B=16)),        # D = 3 chunks: the loop's tail
+    ("mlr_tiny", 7, 3, dict(J=37, D=203, P=3, B=5)),        # D % 32 != 0: the switch is ignored
+])
+def test_split_bf16_scores(sfb, name, seed, steps, override):
+    """fp32 scores computed as six bf16 term products per product (plan bit 2): same parity bar
+    as the fp32 matrix-core kernels, for all steps of a chain."""
+    wl = workloads.make(name, seed=seed, **override)
+    worst = run_chain(wl, steps, TOL32, check_every=1 if steps <= 20 else 5, plan=dict(fwd_dma=5))
+    print(f"{name} {override}: split-bf16 scores, worst error/allowance {worst}")
+
+
+def test_split_bf16_scores_are_as_accurate_as_fp32_mfma(sfb):
+    """The exact three-way split keeps fp32's 24 bits: against the fp64 oracle the split-bf16
+    scores are at least as close as the fp32 matrix-core scores."""
+    dev = "cuda:0"
+    wl = workloads.make("mlr_medium")
+    b = wl.batch(0)
+    db, dy = to_device(wl, b, dev)
+    want = oracle.scores(wl.W0.astype(np.float64), b["A"].astype(np.float64))
+    errs = {}
+    for mode in (1, 5):
+        ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+        ctx.set_plan(fwd_dma=mode)
+        W = torch.from_numpy(wl.W0).to(dev)
+        U, V, loss = alloc_factors(wl, dev)
+        ctx.compute_factors(W, db, dy, U, V, loss)
+        ctx.sync()
+        # the loss is logsumexp(z) - z_y: compare it and the factors, both smooth functions of the scores
+        fo, Uo = oracle.loss_and_u(wl.model, want, b["y"])
+        errs[mode] = (float(np.abs(U.cpu().numpy() - Uo).max()), float(np.abs(loss.cpu().numpy() - fo).max()))
+        ctx.close()
+    print("max abs error of (U, loss): fp32 mfma", errs[1], " split-bf16", errs[5])
+    assert errs[5][0] <= 2.0 * errs[1][0] + 1e-9 and errs[5][1] <= 2.0 * errs[1][1] + 1e-7
