@@ -195,7 +195,8 @@ SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32
  * instead of from the CSR entries; bit 2 = fp32 scores on the bf16 matrix cores, every fp32 operand split
  * exactly into three bf16 terms and every product taken as its six leading term products (error
  * at the level of one fp32 rounding; full batch and 16-byte aligned rows only, else ignored);
- * < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
+ * bit 3 = the same for the fp32 reconstruction (J, D multiples of 4, N a multiple of 32, no dead
+ * workers, else ignored); < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
  * query sfb_workspace_bytes again.  SFB_EINVAL for a value outside the table. */
 SFB_API sfb_status sfb_set_plan(sfb_ctx *ctx, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k,
                                 int32_t recon_variant, int32_t fwd_dma);

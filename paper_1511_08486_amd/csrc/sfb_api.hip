@@ -36,6 +36,7 @@ struct sfb_ctx {
     FwdPlan fwd_bf16;              // all N rows on the bf16 matrix cores (bf16 contexts)
     FwdPlan fwd_split;             // all N rows, fp32 operands split into bf16 terms (64 x 128 tiles)
     bool split_scores;             // use it where the shape allows
+    bool split_recon;              // reconstruction with split-bf16 products where the shape allows
     ReconPlan recon;
     void* ws;
     size_t ws_bytes;
@@ -222,6 +223,8 @@ sfb_status recon_launch(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64
     if (r.bf16) {
         if (c->ws == nullptr || c->ws_bytes < workspace_need(c)) return SFB_EWORKSPACE;
         e = launch_reconstruct_bf16(r, (char*)c->ws + scores_need(c), c->stream);
+    } else if (c->split_recon && reconstruct_split_ok(r)) {
+        e = launch_reconstruct_split(r, c->stream);
     } else {
         e = launch_reconstruct(r, c->recon, c->stream);
     }
@@ -264,6 +267,7 @@ sfb_status sfb_create(sfb_ctx** out, sfb_model m, int64_t J, int64_t D, int32_t 
         c->fwd_split = sp;
     }
     c->split_scores = false;
+    c->split_recon = false;
     c->recon = plan_reconstruct(J, D, (int64_t)P * B);
     c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->timing = false; c->sparse_forward = true;
     *out = c;
@@ -401,6 +405,7 @@ sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_
     if (fwd_dma >= 0) p.dma = (fwd_dma & 1) != 0;
     if (fwd_dma >= 0) c->sparse_forward = (fwd_dma & 2) == 0;   // bit 1 set: dense scores for CSR input
     if (fwd_dma >= 0) c->split_scores = (fwd_dma & 4) != 0;     // bit 2 set: fp32 scores as split-bf16 products
+    if (fwd_dma >= 0) c->split_recon = (fwd_dma & 8) != 0;      // bit 3 set: the reconstruction likewise
     finish_forward_plan(&p, (int64_t)c->P * c->B, c->J, c->D);
     c->fwd_all = p;
     if (recon_variant >= 0) c->recon = plan_reconstruct_variant(c->J, c->D, recon_variant);

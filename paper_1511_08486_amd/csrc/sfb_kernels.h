@@ -113,6 +113,9 @@ struct ReconArgs {
     bool use_mask, bf16;
 };
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s);
+// fp32 reconstruction as six bf16 term products per product (sfb_reconstruct_split.hip); 128 x 128 tiles
+bool reconstruct_split_ok(const ReconArgs& a);
+hipError_t launch_reconstruct_split(const ReconArgs& a, hipStream_t s);
 
 // bf16-feature path on the bf16 matrix cores (sfb_bf16.hip)
 bool forward_bf16_ok(const FwdArgs& a);                       // alignment / shape the DMA kernel needs

@@ -276,6 +276,40 @@ def test_split_bf16_scores(sfb, name, seed, steps, override):
     print(f"{name} {override}: split-bf16 scores, worst error/allowance {worst}")
 
 
+@pytest.mark.parametrize("name,seed,steps,override", [
+    ("mlr_medium", 0, 100, {}),
+    ("dml", 1, 20, {}),
+    ("l2svm", 0, 5, {}),
+    ("mlr_tiny", 5, 3, dict(J=132, D=260, P=2, B=32)),      # ragged tiles in both directions
+    ("mlr_tiny", 6, 3, dict(J=64, D=128, P=3, B=32)),       # N = 96 = 3 chunks: the loop's tail
+    ("mlr_tiny", 8, 3, dict(J=8, D=4, P=1, B=32)),          # one chunk, tile far larger than W
+    ("mlr_tiny", 7, 3, dict(J=37, D=203, P=3, B=5)),        # J % 4 != 0, N % 32 != 0: the switch is ignored
+])
+def test_split_bf16_scores_and_reconstruction(sfb, name, seed, steps, override):
+    """Both contractions as split-bf16 products (plan bits 2 and 3), whole chains against the oracle."""
+    wl = workloads.make(name, seed=seed, **override)
+    worst = run_chain(wl, steps, TOL32, check_every=1 if steps <= 20 else 5, plan=dict(fwd_dma=13))
+    print(f"{name} {override}: split-bf16 scores and reconstruction, worst error/allowance {worst}")
+
+
+def test_split_bf16_reconstruction_with_a_dead_worker_falls_back(sfb):
+    """A mask of live workers is not covered by the split kernel: the call must still be right."""
+    dev = "cuda:0"
+    wl = workloads.make("mlr_tiny", seed=9, J=64, D=128, P=4, B=32)
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+    ctx.set_plan(fwd_dma=13)
+    b = wl.batch(0)
+    db, dy = to_device(wl, b, dev)
+    W = torch.from_numpy(wl.W0).to(dev)
+    U, V, _ = alloc_factors(wl, dev)
+    active = [1, 0, 1, 1]
+    ctx.step(W, db, dy, U, V, wl.eta, active=active)
+    ctx.sync()
+    _, _, want, _ = oracle.step(wl.model, wl.W0, b, wl.P, wl.B, wl.eta, active=active)
+    assert_close(W.cpu().numpy(), want, TOL32, "W, split plan, dead worker")
+    ctx.close()
+
+
 def test_split_bf16_scores_are_as_accurate_as_fp32_mfma(sfb):
     """The exact three-way split keeps fp32's 24 bits: against the fp64 oracle the split-bf16
     scores are at least as close as the fp32 matrix-core scores."""
