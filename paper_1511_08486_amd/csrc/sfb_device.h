@@ -149,6 +149,23 @@ __device__ __forceinline__ void store4(bf16_t* __restrict__ row, int64_t col, in
     }
 }
 
+// Two fp32 values -> two bf16 (round to nearest even) packed in one word, first value in the low half.
+typedef float sfb_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 sfb_bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
+    const sfb_f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, sfb_bf16x2));
+}
+// Exact three-way split of two fp32 values into bf16 terms, x = h + m + l (3 x 8 significand bits
+// cover fp32's 24; both differences are exact in fp32).  Outputs are packed pairs as cvt_pk_bf16.
+__device__ __forceinline__ void split3_pair(float x0, float x1, uint32_t& h, uint32_t& m, uint32_t& l) {
+    h = cvt_pk_bf16(x0, x1);
+    const float r0 = x0 - __uint_as_float(h << 16), r1 = x1 - __uint_as_float(h & 0xffff0000u);
+    m = cvt_pk_bf16(r0, r1);
+    const float s0 = r0 - __uint_as_float(m << 16), s1 = r1 - __uint_as_float(m & 0xffff0000u);
+    l = cvt_pk_bf16(s0, s1);
+}
+
 // LDS-DMA: one wavefront-wide instruction moves 64 x 16 bytes from per-lane global addresses
 // to LDS; lane i lands at lds_addr + 16*i.  lds_addr must be wavefront-uniform (it travels in
 // M0).  The compiler does not see the LDS write: the caller orders it by hand with

@@ -23,7 +23,6 @@
 namespace sfb {
 
 typedef __bf16 sbf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 sbf16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t su32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kSsThreads = 256, kSsBM = 64, kSsBN = 128, kSsBK = 32;
@@ -38,18 +37,10 @@ __device__ __forceinline__ void ss_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// x = h + m + l exactly (up to the 24 bits of x), each term a bf16 (round to nearest even)
-__device__ __forceinline__ void split3(f32x4 x, sbf16x4& h, sbf16x4& m, sbf16x4& l) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const __bf16 hh = (__bf16)x[e];
-        const float r1 = x[e] - (float)hh;
-        const __bf16 mm = (__bf16)r1;
-        const float r2 = r1 - (float)mm;
-        h[e] = hh;
-        m[e] = mm;
-        l[e] = (__bf16)r2;
-    }
+// four consecutive k of one row -> 8 bytes per plane
+__device__ __forceinline__ void split3_x4(f32x4 x, uint2& h, uint2& m, uint2& l) {
+    split3_pair(x[0], x[1], h.x, m.x, l.x);
+    split3_pair(x[2], x[3], h.y, m.y, l.y);
 }
 
 template <bool DIFF>
@@ -112,11 +103,11 @@ __global__ __launch_bounds__(kSsThreads) void scores_split_kernel(
         for (int i = 0; i < A_LD; ++i) {
             f32x4 x = r.a[i];
             if (DIFF) x -= r.a2[i];
-            sbf16x4 h, m, l;
-            split3(x, h, m, l);
-            *reinterpret_cast<sbf16x4*>(sa + i * ROW_STEP * ROWB) = h;
-            *reinterpret_cast<sbf16x4*>(sa + kSsPlaneA + i * ROW_STEP * ROWB) = m;
-            *reinterpret_cast<sbf16x4*>(sa + 2 * kSsPlaneA + i * ROW_STEP * ROWB) = l;
+            uint2 h, m, l;
+            split3_x4(x, h, m, l);
+            *reinterpret_cast<uint2*>(sa + i * ROW_STEP * ROWB) = h;
+            *reinterpret_cast<uint2*>(sa + kSsPlaneA + i * ROW_STEP * ROWB) = m;
+            *reinterpret_cast<uint2*>(sa + 2 * kSsPlaneA + i * ROW_STEP * ROWB) = l;
             if (write_v) {                                // v_i = a_i (or x_i - y_i)
                 const int row = m0 + r0 + i * ROW_STEP;
                 if (row < M)
@@ -125,11 +116,11 @@ __global__ __launch_bounds__(kSsThreads) void scores_split_kernel(
         }
 #pragma unroll
         for (int i = 0; i < W_LD; ++i) {
-            sbf16x4 h, m, l;
-            split3(r.w[i], h, m, l);
-            *reinterpret_cast<sbf16x4*>(sb + i * ROW_STEP * ROWB) = h;
-            *reinterpret_cast<sbf16x4*>(sb + kSsPlaneB + i * ROW_STEP * ROWB) = m;
-            *reinterpret_cast<sbf16x4*>(sb + 2 * kSsPlaneB + i * ROW_STEP * ROWB) = l;
+            uint2 h, m, l;
+            split3_x4(r.w[i], h, m, l);
+            *reinterpret_cast<uint2*>(sb + i * ROW_STEP * ROWB) = h;
+            *reinterpret_cast<uint2*>(sb + kSsPlaneB + i * ROW_STEP * ROWB) = m;
+            *reinterpret_cast<uint2*>(sb + 2 * kSsPlaneB + i * ROW_STEP * ROWB) = l;
         }
     };
 

@@ -20,7 +20,6 @@
 namespace sfb {
 
 typedef __bf16 rbf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 rbf16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t ru32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRsThreads = 512, kRsBM = 128, kRsBN = 128, kRsBK = 32;
@@ -78,25 +77,15 @@ __global__ __launch_bounds__(kRsThreads, 2) void reconstruct_split_kernel(
     };
     auto stage = [&](const Chunk& r, int st) {
         unsigned char* base = rs_lds + st * kRsStageBytes + lds_block;
-        // x = h + m + l exactly, each a bf16 (round to nearest even; both differences are exact in fp32)
-        rbf16x4 h[4], m[4], l[4];                                      // [column e][pair i]
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float x = r.x[i][e];
-                const __bf16 hh = (__bf16)x;
-                const float r1 = x - (float)hh;
-                const __bf16 mm = (__bf16)r1;
-                h[e][i] = hh;
-                m[e][i] = mm;
-                l[e][i] = (__bf16)(r1 - (float)mm);
-            }
+        // per column e: the four pairs' terms as two packed words (pairs 0-1, 2-3), 8 bytes per plane
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            *reinterpret_cast<rbf16x4*>(base + e * ROWB) = h[e];
-            *reinterpret_cast<rbf16x4*>(base + kRsPlane + e * ROWB) = m[e];
-            *reinterpret_cast<rbf16x4*>(base + 2 * kRsPlane + e * ROWB) = l[e];
+            uint2 h, m, l;
+            split3_pair(r.x[0][e], r.x[1][e], h.x, m.x, l.x);
+            split3_pair(r.x[2][e], r.x[3][e], h.y, m.y, l.y);
+            *reinterpret_cast<uint2*>(base + e * ROWB) = h;
+            *reinterpret_cast<uint2*>(base + kRsPlane + e * ROWB) = m;
+            *reinterpret_cast<uint2*>(base + 2 * kRsPlane + e * ROWB) = l;
         }
     };
 
