@@ -219,6 +219,29 @@ def main():
         "stream_copy": {"GB/s": copy_gbs, "bytes_per_launch": copy_bytes,
                         "note": "plain float4 copy kernel, 256 MiB read + 256 MiB written per launch"},
     }
+    if wl.dtype == "f32" and not args.plan and not args.graph:
+        # informational second line: the same steps with both contractions taken as split-bf16 products on the
+        # bf16 matrix cores (opt-in plan bits 2 and 3; fp32-level error, same parity tests).  Not the headline.
+        alt = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
+        alt.set_plan(fwd_dma=13)
+        W.copy_(W0)
+        for t in range(args.warmup):
+            b, y = pool[t % len(pool)]
+            alt.step(W, b, y, U, V, wl.eta)
+        torch.cuda.synchronize()
+        W.copy_(W0)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for t in range(args.steps):
+            b, y = pool[t % len(pool)]
+            alt.step(W, b, y, U, V, wl.eta)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t1
+        assert bool(torch.isfinite(W).all()), "W is not finite after the split-bf16 steps"
+        out["alt_plan"] = {"name": "split-bf16 contractions (sfb_set_plan fwd_dma=13)", "value": wl.N * args.steps / el,
+                           "unit": "samples/s", "ms_per_step": el / args.steps * 1e3,
+                           "note": "fp32 operands split exactly into three bf16 terms, six term products per product"}
+        alt.close()
     if args.objective_every > 0:
         # objective vs samples on the synthetic data (Section 6's third panel), from the loss the factor kernel emits
         W.copy_(W0)
