@@ -13,8 +13,8 @@
 // k order, so the order itself is immaterial).
 //   scores (Section 2, z = W a):      A = features [N][D] bf16, B = W [J][D] fp32, widened
 //                                     operand rounded to bf16 (RNE) after the LDS read;
-//                                     epilogue stores a split-K partial of Z and, for class
-//                                     block 0, passes the feature tile on to V (v_i = a_i).
+//                                     epilogue stores a split-K partial of Z; the feature tiles
+//                                     are passed on to V (v_i = a_i), a share per class block.
 //   reconstruct (Section 3 + 2.1):    A = (alpha u)^T [J][N] bf16, B = v^T [D][N] bf16, both
 //                                     produced by transpose_pack_kernel from the received
 //                                     factors; epilogue is the read-modify-write W += C.
@@ -199,8 +199,9 @@ __global__ __launch_bounds__(WGM * WGN * 64, WPS) void nt_bf16_kernel(
             }
         }
     };
-    // v_i = a_i: the staged feature items go on to V (score pass, class block 0 only)
-    const bool write_v = (EPI == kStoreZ) && (Vout != nullptr) && (nb == 0);
+    // v_i = a_i: the staged feature items go on to V (score pass); the class blocks share the job,
+    // block nb takes the chunks c with c % n_nb == nb
+    const bool write_v = (EPI == kStoreZ) && (Vout != nullptr);
     auto copy_v = [&](int chunk, int st) {
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, WPS) void nt_bf16_kernel(
         else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
         if (c + NST - 1 < n_chunks) issue(c + NST - 1, (st + NST - 1) % NST);
-        if (write_v) copy_v(c, st);
+        if (write_v && (c % n_nb) == nb) copy_v(c, st);
         compute(st);
     };
     static_assert(NST == 3 || NST == 4, "ring depth");

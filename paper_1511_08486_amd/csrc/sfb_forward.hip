@@ -248,7 +248,8 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
     const int n0 = nb * BM, j0 = jb * BN;
     const int k_begin = ks * k_slice;
     const int n_chunks = (min(D, k_begin + k_slice) - k_begin) / BK;   // host: D % BK == 0
-    const bool write_v = (V != nullptr) && (jb == 0);
+    // v_i = a_i is written once: the class blocks share the job, block jb takes the chunks c with c % n_jb == jb
+    const bool write_v = V != nullptr;
 
     // slot s = tid + i*256 of a tile holds row s/8, physical item s%8 = logical item ^ f(row)
     const float* pa[A_LD];
@@ -336,7 +337,7 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
             }
         }
     };
-    // v_i = a_i: pass the staged feature items on to V (class block 0 only)
+    // v_i = a_i: pass the staged feature items on to V
     auto copy_v = [&](int chunk, int st) {
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_dma_kernel(
         if (c + 1 < n_chunks) wait_vmcnt<DMAS>(); else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
         if (c + 2 < n_chunks) issue(c + 2, (st + 2) % NST);
-        if (write_v) copy_v(c, st);
+        if (write_v && (c % n_jb) == jb) copy_v(c, st);
         compute(st);
     };
     int c = 0;

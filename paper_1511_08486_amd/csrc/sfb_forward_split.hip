@@ -82,7 +82,8 @@ __global__ __launch_bounds__(kSsThreads) void scores_split_kernel(
         w_off[i] = (uint32_t)min(r0 + i * ROW_STEP, N - 1 - n0) * (uint32_t)ldw * 4u + 16u * c0;
     // where a lane's four values land inside a plane (piece i: ROW_STEP rows further down, same swizzle)
     const int lds_piece = r0 * ROWB + 16 * ((c0 >> 1) ^ ss_swz(r0)) + 8 * (c0 & 1);
-    const bool write_v = (Vout != nullptr) && (nb == 0);
+    // the class blocks share the copy: block nb takes the chunks c with c % n_nb == nb
+    const bool write_v = Vout != nullptr;
 
     struct Chunk { f32x4 a[A_LD]; f32x4 a2[DIFF ? A_LD : 1]; f32x4 w[W_LD]; };
     auto fetch = [&](Chunk& r, int chunk) {
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kSsThreads) void scores_split_kernel(
             *reinterpret_cast<uint2*>(sa + i * ROW_STEP * ROWB) = h;
             *reinterpret_cast<uint2*>(sa + kSsPlaneA + i * ROW_STEP * ROWB) = m;
             *reinterpret_cast<uint2*>(sa + 2 * kSsPlaneA + i * ROW_STEP * ROWB) = l;
-            if (write_v) {                                // v_i = a_i (or x_i - y_i)
+            if (write_v && (chunk % n_nb) == nb) {        // v_i = a_i (or x_i - y_i)
                 const int row = m0 + r0 + i * ROW_STEP;
                 if (row < M)
                     *reinterpret_cast<f32x4*>(Vout + (int64_t)row * ldv + k_begin + chunk * BK + 4 * c0) = x;
