@@ -6,8 +6,9 @@
 // BM x BN output tile over one slice of D and writes a partial sum; the factor kernel
 // adds the slices in a fixed order (deterministic, no atomics, no zero fill).
 //
-// The workgroups with class-block 0 also write v_i = a_i (DML: x_i - y_i) into V:
-// the features pass through registers here anyway, so the "write_v" copy of
+// The workgroups also write v_i = a_i (DML: x_i - y_i) into V, each class block its share of
+// the chunks of D (one block doing all of it would be the straggler every other workgroup
+// waits for): the features pass through the compute unit anyway, so the "write_v" copy of
 // Section 4.2 costs no extra read.
 //
 // MFMA: v_mfma_f32_32x32x2_f32.  Lane l supplies A[l%32][l/32] and B[l/32][l%32] and
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
     const int k_begin = ks * k_slice;
     const int k_end = min(D, k_begin + k_slice);
     const int n_chunks = (k_end - k_begin + BK - 1) / BK;
-    const bool write_v = (V != nullptr) && (jb == 0);
+    const bool write_v = V != nullptr;   // shared by the class blocks: block jb takes the chunks c with c % n_jb == jb
 
     using RawA = typename RawOf<TIn>::type;
     struct Stage { RawA a[A_LD]; RawA a2[DIFF ? A_LD : 1]; f32x4 b[B_LD]; };
@@ -95,9 +96,9 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
             }
         }
     };
-    // widen / subtract / zero out-of-range elements on the way into LDS; the workgroups of
-    // class block 0 also deliver v_i here
+    // widen / subtract / zero out-of-range elements on the way into LDS; v_i is delivered here too
     auto stage = [&](const Stage& r, int buf, int k0) {
+        const bool my_v = write_v && (((k0 - k_begin) / BK) % n_jb) == jb;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
             const int idx = tid + i * kFwdThreads;
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
             const bool in = row < n_rows && col < k_end;   // FAST: k_end is a multiple of 4
             if (FAST) v = in ? v : zero4;
             *reinterpret_cast<f32x4*>(&As[buf * BM * LS + rr * LS + cc]) = v;
-            if (write_v && in) {
+            if (my_v && in) {
                 if (FAST) *reinterpret_cast<RawA*>(V + (int64_t)row * ldv + col) = to_raw<TIn>(v);
                 else store4(V + (int64_t)row * ldv, col, k_end, vec_v, v);
             }
