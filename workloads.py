@@ -30,6 +30,12 @@ CONFIGS = {
                        density=0.02),
 }
 
+SDCA_CONFIGS = {
+    # name: classes J, features D, data samples N_data, P workers, B samples per worker, l2 weight lam, steps, dtype
+    "sdca_tiny":   dict(J=10,   D=100,  n_data=256,  P=4, B=16, lam=1e-2, steps=8,  dtype="f32"),
+    "sdca_medium": dict(J=1000, D=4096, n_data=8192, P=8, B=64, lam=1e-4, steps=20, dtype="f32"),
+}
+
 DML_CLUSTERS = 50
 DML_CENTRE_VAR = 2.4   # times 1/D
 DML_POINT_VAR = 1.0    # times 1/D
@@ -185,3 +191,45 @@ def ssp_proposals(P, n_events, seed=0, p_step=0.45):
             q = int((p + 1 + rng.integers(P - 1)) % P) if P > 1 else p
             events.append(("deliver", p, q, int(rng.integers(1, 3))))
     return events
+
+
+@dataclass
+class SdcaWorkload:
+    """A fixed data set (SDCA keeps one dual vector per data sample) and, per step, the P*B
+    distinct sample indices the workers pick (worker-major).  Class-dependent feature means
+    make the problem learnable; no arithmetic of the method is applied here."""
+    name: str
+    J: int
+    D: int
+    n_data: int
+    P: int
+    B: int
+    lam: float
+    steps: int
+    dtype: str
+    A: np.ndarray                   # [n_data, D] float32 (bf16-representable when dtype == "bf16")
+    y: np.ndarray                   # [n_data] int32
+    picks: list = field(default_factory=list)     # per step: [P*B] int32, distinct
+
+    @property
+    def N(self):
+        return self.P * self.B
+
+    def pick(self, t):
+        return self.picks[t % len(self.picks)]
+
+
+def make_sdca(name, seed=0, **override):
+    """Draw order: class means, labels, features, then one index set per step."""
+    cfg = dict(SDCA_CONFIGS[name])
+    cfg.update(override)
+    rng = np.random.default_rng(seed)
+    J, D, n_data, P, B = cfg["J"], cfg["D"], cfg["n_data"], cfg["P"], cfg["B"]
+    if P * B > n_data:
+        raise ValueError("a step picks P*B distinct samples: needs P*B <= n_data")
+    means = rng.standard_normal((J, D)) / np.sqrt(D)
+    y = rng.integers(0, J, size=n_data).astype(np.int32)
+    a = means[y] + rng.standard_normal((n_data, D)) / np.sqrt(D)
+    picks = [rng.choice(n_data, size=P * B, replace=False).astype(np.int32) for _ in range(cfg["steps"])]
+    return SdcaWorkload(name=name, J=J, D=D, n_data=n_data, P=P, B=B, lam=cfg["lam"], steps=cfg["steps"],
+                        dtype=cfg["dtype"], A=_cast_features(a, cfg["dtype"]), y=y, picks=picks)
