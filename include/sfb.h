@@ -161,6 +161,45 @@ SFB_API sfb_status sfb_step(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_batch
                     float *U, int64_t ldu, void *V, int64_t ldv, float *loss, float eta,
                     const uint8_t *active);
 
+/*
+ * SFB driven by stochastic dual coordinate ascent (Section 2.1, "Stochastic DCA") for the
+ * l2-regularised multiclass logistic regression, h(W) = lam/2 ||W||_F^2 (SFB_MLR contexts only).
+ * Every data sample i owns a dual vector u_i in R^J; the primal matrix is tied to them by
+ * W = grad h*(Z) = Z / lam with Z = (1/n_data) sum_i u_i a_i^T.  One iteration picks P*B
+ * DISTINCT data samples (batch row r is data sample sample[r]); for each of them, with the
+ * scores z = W a at the iteration's start,
+ *     delta u_i = s * (u_i - (e_y - softmax(z))),     u_i <- u_i - delta u_i,
+ * (the step of proximal SDCA: a fraction s in (0, 1] of the way to the dual vector that is
+ * optimal for the current scores), and the pair (delta u_i, a_i) is the sufficient factor:
+ *     W <- W - 1/(lam n_data) * sum_i delta u_i a_i^T
+ * which is sfb_reconstruct_apply with eta = 1 and scale = 1/(lam n_data).
+ * Start from dual = 0 and W = 0 (or any pair that satisfies the tie above).
+ *   dual    DEVICE [n_data][ld_dual] fp32, updated in place at the picked rows.
+ *   sample  DEVICE [N] int32 in [0, n_data), distinct within the call (not checked: two rows
+ *           naming one sample race on its dual vector).
+ *   conj    DEVICE [n_data] fp32 or NULL: entry sample[r] receives f*(-u) = sum_j p_j log p_j,
+ *           p = e_y - u, of the updated dual vector (the sample's term of the dual objective).
+ */
+typedef struct sfb_sdca {
+    float *dual;
+    int64_t ld_dual;
+    int64_t n_data;
+    const int32_t *sample;
+    float *conj;
+    float lam;
+    float s;
+} sfb_sdca;
+/* Factors of one SDCA iteration: U [N][ldu] = delta u_i, V = a_i, loss [N] = f_i(W a_i) or NULL;
+ * the dual vectors of the picked samples are updated.  W is read only.
+ * SFB_EINVAL: null dual / sample, n_data < 1, lam <= 0 or s outside (0, 1] or not finite;
+ * SFB_ESHAPE: ld_dual < J; SFB_EUNSUPPORTED: the context's model is not SFB_MLR. */
+SFB_API sfb_status sfb_sdca_compute_factors(sfb_ctx *ctx, const float *W, int64_t ldw, const sfb_batch *batch,
+                                    const int32_t *y, const sfb_sdca *sdca, float *U, int64_t ldu,
+                                    void *V, int64_t ldv, float *loss);
+/* sfb_sdca_compute_factors followed by the reconstruction above: one full SDCA iteration. */
+SFB_API sfb_status sfb_sdca_step(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_batch *batch, const int32_t *y,
+                         const sfb_sdca *sdca, float *U, int64_t ldu, void *V, int64_t ldv, float *loss);
+
 /* What the context was created with; any pointer may be NULL. */
 SFB_API sfb_status sfb_shape(const sfb_ctx *ctx, int64_t *J, int64_t *D, int32_t *P, int32_t *B,
                      int32_t *input_dtype);

@@ -35,6 +35,9 @@ Readings (the paper leaves both open):
         g_i = -grad f_i(z_i) = e_{y_i} - softmax(z_i),     delta u_i = s (u_i - g_i),
     with s supplied by the caller; ``safe_fraction`` gives a value for which (D) cannot
     increase.  The samples of one iteration must be distinct.
+Two forms are kept on purpose: ``step`` walks the picked samples one at a time, forming every
+rank-1 update explicitly (the definition); ``step_matrix`` does the same arithmetic with
+matrix products so that it finishes at larger sizes.  A test pins one to the other.
 Starting point: U = 0 (feasible: e_y - 0 is a vertex of the simplex), hence Z = 0, W = 0.
 """
 from __future__ import annotations
@@ -146,5 +149,24 @@ class SdcaMlrOracle:
         for n, i in enumerate(picked):
             self.U[i] = self.U[i] - delta[n]
             self.Z = self.Z - np.outer(delta[n], self.A[i]) / self.N
+        self.W = self.grad_h_conj(self.Z)
+        return delta, losses
+
+    def step_matrix(self, picked, s):
+        """Same iteration as ``step`` with matrix products instead of per-sample loops."""
+        picked = np.asarray(picked, dtype=np.int64)
+        if np.unique(picked).size != picked.size:
+            raise ValueError("the samples of one iteration must be distinct")
+        A, y = self.A[picked], self.y[picked]
+        Zs = A @ self.W.T                                        # [n, J] scores at the start
+        m = Zs.max(axis=1, keepdims=True)
+        e = np.exp(Zs - m)
+        lse = m[:, 0] + np.log(e.sum(axis=1))
+        losses = lse - Zs[np.arange(picked.size), y]
+        G = -e / e.sum(axis=1, keepdims=True)
+        G[np.arange(picked.size), y] += 1.0                      # optimal dual vectors
+        delta = s * (self.U[picked] - G)
+        self.U[picked] = self.U[picked] - delta
+        self.Z = self.Z - delta.T @ A / self.N
         self.W = self.grad_h_conj(self.Z)
         return delta, losses

@@ -27,6 +27,11 @@ class sfb_batch(C.Structure):
                 ("nnz", C.c_int64)]
 
 
+class sfb_sdca(C.Structure):
+    _fields_ = [("dual", C.c_void_p), ("ld_dual", C.c_int64), ("n_data", C.c_int64), ("sample", C.c_void_p),
+                ("conj", C.c_void_p), ("lam", C.c_float), ("s", C.c_float)]
+
+
 def _load():
     path = library_path()
     if not os.path.exists(path):
@@ -38,6 +43,7 @@ def _load():
         raise ImportError(f"cannot load {path}: {e}") from e
     vp, i64, i32, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_float
     pb = C.POINTER(sfb_batch)
+    pd = C.POINTER(sfb_sdca)
     sigs = {
         "sfb_create": (C.c_int, [C.POINTER(vp), C.c_int, i64, i64, i32, i32, C.c_int, vp]),
         "sfb_destroy": (None, [vp]),
@@ -58,6 +64,8 @@ def _load():
         "sfb_reset_timing": (C.c_int, [vp]),
         "sfb_reconstruct_apply_worker": (C.c_int, [vp, vp, i64, vp, i64, vp, i64, i32, f32, f32]),
         "sfb_shape": (C.c_int, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
+        "sfb_sdca_compute_factors": (C.c_int, [vp, vp, i64, pb, vp, pd, vp, i64, vp, i64, vp]),
+        "sfb_sdca_step": (C.c_int, [vp, vp, i64, pb, vp, pd, vp, i64, vp, i64, vp]),
         "sfb_ssp_create": (C.c_int, [C.POINTER(vp), vp, i32, C.POINTER(vp), i64, vp, i64, vp, i64, i32]),
         "sfb_ssp_destroy": (None, [vp]),
         "sfb_ssp_worker_step": (C.c_int, [vp, i32, pb, vp, f32, vp, C.POINTER(i32)]),
@@ -203,6 +211,24 @@ class Sfb:
         self._check(lib.sfb_step(self._ctx, W.data_ptr(), W.stride(0), C.byref(b), y.data_ptr(), U.data_ptr(),
                                  U.stride(0), V.data_ptr(), V.stride(0), _ptr(loss), float(eta), ptr),
                     "sfb_step")
+
+    # -- SDCA ------------------------------------------------------------------
+    @staticmethod
+    def _sdca(dual, sample, lam, s, conj):
+        return sfb_sdca(dual.data_ptr(), dual.stride(0), dual.shape[0], sample.data_ptr(), _ptr(conj), float(lam),
+                        float(s))
+
+    def sdca_compute_factors(self, W, batch, y, dual, sample, lam, s, U, V, loss=None, conj=None):
+        b, d = batch.c_struct(), self._sdca(dual, sample, lam, s, conj)
+        self._check(lib.sfb_sdca_compute_factors(self._ctx, W.data_ptr(), W.stride(0), C.byref(b), y.data_ptr(),
+                                                 C.byref(d), U.data_ptr(), U.stride(0), V.data_ptr(), V.stride(0),
+                                                 _ptr(loss)), "sfb_sdca_compute_factors")
+
+    def sdca_step(self, W, batch, y, dual, sample, lam, s, U, V, loss=None, conj=None):
+        b, d = batch.c_struct(), self._sdca(dual, sample, lam, s, conj)
+        self._check(lib.sfb_sdca_step(self._ctx, W.data_ptr(), W.stride(0), C.byref(b), y.data_ptr(), C.byref(d),
+                                      U.data_ptr(), U.stride(0), V.data_ptr(), V.stride(0), _ptr(loss)),
+                    "sfb_sdca_step")
 
     def sync(self):
         self._check(lib.sfb_sync(self._ctx), "sfb_sync")

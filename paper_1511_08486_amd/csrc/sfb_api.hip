@@ -134,7 +134,7 @@ sfb_status check_batch(const sfb_ctx* c, const sfb_batch* b, const int32_t* y) {
 // Factors of `n_rows` samples whose outputs start at row `row0` of U, V, loss.
 sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t ldw, const sfb_batch* b,
                         const int32_t* y, int64_t row0, int n_rows, float* U, int64_t ldu, void* V,
-                        int64_t ldv, float* loss) {
+                        int64_t ldv, float* loss, const sfb_sdca* sdca = nullptr) {
     if (c->ws == nullptr || c->ws_bytes < workspace_need(c)) return SFB_EWORKSPACE;
     const bool bf16 = c->dtype == SFB_BF16;
     const size_t vsz = bf16 ? 2 : 4;
@@ -185,11 +185,24 @@ sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t
     g.zp = (const float*)c->ws; g.ldz = ldz; g.zstride = f.zstride; g.split_k = sparse_scores ? 1 : used.split_k;
     g.y = y; g.u = U + row0 * ldu; g.ldu = ldu; g.loss = loss ? loss + row0 : nullptr;
     g.n_rows = n_rows; g.J = (int)c->J; g.model = (Model)c->model;
+    if (sdca) {
+        const bool vec = ((uintptr_t)sdca->dual % 16) == 0 && (sdca->ld_dual % 4) == 0;
+        g.sdca = SdcaDev{sdca->sample, sdca->dual, sdca->ld_dual, sdca->conj, sdca->s, vec};
+    }
     {
         Timed t(c, 1);
         hipError_t e = launch_factor(g, c->stream);
         if (e != hipSuccess) return hip_fail(c, e);
     }
+    return SFB_OK;
+}
+
+sfb_status check_sdca(const sfb_ctx* c, const sfb_sdca* d) {
+    if (!d || !d->dual || !d->sample || d->n_data < 1) return SFB_EINVAL;
+    if (!std::isfinite(d->lam) || !(d->lam > 0.f) || !std::isfinite(d->s) || !(d->s > 0.f) || d->s > 1.f)
+        return SFB_EINVAL;
+    if (d->ld_dual < c->J) return SFB_ESHAPE;
+    if (c->model != SFB_MLR) return SFB_EUNSUPPORTED;
     return SFB_OK;
 }
 
@@ -349,6 +362,29 @@ sfb_status sfb_step(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, c
     s = factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss);
     if (s != SFB_OK) return s;
     return recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active);
+}
+
+sfb_status sfb_sdca_compute_factors(sfb_ctx* c, const float* W, int64_t ldw, const sfb_batch* batch,
+                                    const int32_t* y, const sfb_sdca* sdca, float* U, int64_t ldu, void* V,
+                                    int64_t ldv, float* loss) {
+    sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
+    if (s != SFB_OK) return s;
+    s = check_batch(c, batch, y);
+    if (s != SFB_OK) return s;
+    s = check_sdca(c, sdca);
+    if (s != SFB_OK) return s;
+    return factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss, sdca);
+}
+
+sfb_status sfb_sdca_step(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, const int32_t* y,
+                         const sfb_sdca* sdca, float* U, int64_t ldu, void* V, int64_t ldv, float* loss) {
+    if (!c || !sdca) return SFB_EINVAL;
+    // Z <- Z - (1/n_data) sum delta u a^T and W = Z / lam, folded into one scale (Section 2.1)
+    const float scale = (float)(1.0 / ((double)sdca->lam * (double)sdca->n_data));
+    if (!std::isfinite(scale)) return SFB_EINVAL;
+    sfb_status s = sfb_sdca_compute_factors(c, W, ldw, batch, y, sdca, U, ldu, V, ldv, loss);
+    if (s != SFB_OK) return s;
+    return recon_launch(c, W, ldw, U, ldu, V, ldv, 1.0f, scale, nullptr);
 }
 
 sfb_status sfb_shape(const sfb_ctx* c, int64_t* J, int64_t* D, int32_t* P, int32_t* B, int32_t* input_dtype) {

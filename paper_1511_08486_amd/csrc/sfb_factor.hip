@@ -8,6 +8,11 @@
 //          f = q or max(0, 1 - q)                         (Section 2, DML paragraph)
 //   L2SVM  t_j = +-1, h = max(0, 1 - t_j z_j), u_j = -2 t_j h, f = sum_j h^2
 // Memory-bound: reads split_k * J and writes J floats per row.
+//
+// SDCA (Section 2.1, "Stochastic DCA") on the logistic loss reuses the MLR row: with
+// r = softmax - e_y (so that -r is the dual vector that is optimal for these scores) and the
+// sample's dual vector u, the factor that is broadcast is delta u = s (u + r), the dual
+// vector becomes u - delta u, and f*(-u) = sum_j p_j log p_j with p = e_y - u.
 #include "sfb_device.h"
 #include "sfb_kernels.h"
 
@@ -37,11 +42,22 @@ __device__ __forceinline__ float group_max(float v, float* red) {
     return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
+__device__ __forceinline__ f32x4 load4_guarded(const float* row, int col, int ncols, bool vec) {
+    if (vec && col + 3 < ncols) return *reinterpret_cast<const f32x4*>(row + col);
+    f32x4 v{0.f, 0.f, 0.f, 0.f};
+    if (col + 0 < ncols) v.x = row[col + 0];
+    if (col + 1 < ncols) v.y = row[col + 1];
+    if (col + 2 < ncols) v.z = row[col + 2];
+    if (col + 3 < ncols) v.w = row[col + 3];
+    return v;
+}
+
 // R = 128-bit items per thread held in registers: covers J <= GROUP * 4 * R.
-template <int MODEL, int GROUP, int R>
+template <int MODEL, int GROUP, int R, bool SDCA>
 __global__ __launch_bounds__(kFactorThreads) void factor_u_kernel(
     const float* __restrict__ Zp, int64_t ldz, int64_t zstride, int split_k, const int32_t* __restrict__ y,
-    float* __restrict__ U, int64_t ldu, float* __restrict__ loss, int n_rows, int J, bool vec_u) {
+    float* __restrict__ U, int64_t ldu, float* __restrict__ loss, int n_rows, int J, bool vec_u, SdcaDev sd) {
+    static_assert(!SDCA || MODEL == kMLR, "the dual update is defined for the logistic loss only");
     __shared__ float red[4];
     constexpr int ROWS = kFactorThreads / GROUP;
     const int t = threadIdx.x % GROUP;
@@ -107,6 +123,27 @@ __global__ __launch_bounds__(kFactorThreads) void factor_u_kernel(
                 z[r][e] = z[r][e] * inv - (col == label ? 1.0f : 0.0f);
             }
         f = m + __logf(sum) - zy;
+        if (SDCA) {
+            const int si = live ? sd.sample[row] : 0;
+            float* drow = sd.dual + (int64_t)si * sd.ldd;
+            float cj = 0.f;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int col = 4 * (t + GROUP * r);
+                f32x4 dv = load4_guarded(drow, col < J ? col : 0, J, sd.vec);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float du = sd.frac * (dv[e] + z[r][e]);
+                    dv[e] -= du;
+                    z[r][e] = du;
+                    const float pj = ((col + e == label) ? 1.0f : 0.0f) - dv[e];
+                    cj += (col + e < J && pj > 0.f) ? pj * __logf(pj) : 0.f;
+                }
+                if (live && col < J) store4(drow, col, J, sd.vec, dv);
+            }
+            cj = group_sum<GROUP>(cj, red);
+            if (live && sd.conj != nullptr && t == 0) sd.conj[si] = cj;
+        }
     } else if (MODEL == kDML) {
         float q = 0.f;
 #pragma unroll
@@ -144,10 +181,11 @@ __global__ __launch_bounds__(kFactorThreads) void factor_u_kernel(
 }
 
 // Any J: three passes over the row's partial sums (they sit in L2 after the contraction).
-template <int MODEL>
+template <int MODEL, bool SDCA>
 __global__ __launch_bounds__(kFactorThreads) void factor_u_long_kernel(
     const float* __restrict__ Zp, int64_t ldz, int64_t zstride, int split_k, const int32_t* __restrict__ y,
-    float* __restrict__ U, int64_t ldu, float* __restrict__ loss, int n_rows, int J) {
+    float* __restrict__ U, int64_t ldu, float* __restrict__ loss, int n_rows, int J, SdcaDev sd) {
+    static_assert(!SDCA || MODEL == kMLR, "the dual update is defined for the logistic loss only");
     __shared__ float red[4];
     const int row = blockIdx.x;      // grid = n_rows exactly
     const int t = threadIdx.x;
@@ -167,14 +205,28 @@ __global__ __launch_bounds__(kFactorThreads) void factor_u_long_kernel(
         for (int col = t; col < J; col += kFactorThreads) sum += __expf(zval(col) - m);
         sum = group_sum<256>(sum, red);
         const float inv = 1.0f / sum;
-        float zy = 0.f;
+        float zy = 0.f, cj = 0.f;
+        const int si = SDCA ? sd.sample[row] : 0;
         for (int col = t; col < J; col += kFactorThreads) {
             const float zc = zval(col);
             if (col == label) zy = zc;
-            U[(int64_t)row * ldu + col] = __expf(zc - m) * inv - (col == label ? 1.0f : 0.0f);
+            float r = __expf(zc - m) * inv - (col == label ? 1.0f : 0.0f);
+            if (SDCA) {
+                float* d = sd.dual + (int64_t)si * sd.ldd + col;
+                const float dv = *d;
+                r = sd.frac * (dv + r);
+                *d = dv - r;
+                const float pj = (col == label ? 1.0f : 0.0f) - (dv - r);
+                cj += pj > 0.f ? pj * __logf(pj) : 0.f;
+            }
+            U[(int64_t)row * ldu + col] = r;
         }
         zy = group_sum<256>(zy, red);
         f = m + __logf(sum) - zy;
+        if (SDCA) {
+            cj = group_sum<256>(cj, red);
+            if (sd.conj != nullptr && t == 0) sd.conj[si] = cj;
+        }
     } else if (MODEL == kDML) {
         float q = 0.f;
         for (int col = t; col < J; col += kFactorThreads) {
@@ -198,30 +250,31 @@ __global__ __launch_bounds__(kFactorThreads) void factor_u_long_kernel(
     if (loss != nullptr && t == 0) loss[row] = f;
 }
 
-template <int MODEL>
+template <int MODEL, bool SDCA>
 static hipError_t launch_factor_m(const FactorArgs& a, hipStream_t s) {
     const bool vec_u = ((uintptr_t)a.u % 16) == 0 && (a.ldu % 4) == 0;
 #define SFB_FACTOR_LAUNCH(GROUP, R)                                                                     \
-    SFB_LAUNCH((factor_u_kernel<MODEL, GROUP, R>),                                              \
+    SFB_LAUNCH((factor_u_kernel<MODEL, GROUP, R, SDCA>),                                                \
                        dim3((a.n_rows + (kFactorThreads / GROUP) - 1) / (kFactorThreads / GROUP)),      \
                        dim3(kFactorThreads), 0, s, a.zp, a.ldz, a.zstride, a.split_k, a.y, a.u, a.ldu,  \
-                       a.loss, a.n_rows, a.J, vec_u)
+                       a.loss, a.n_rows, a.J, vec_u, a.sdca)
     if (a.J <= 64 * 4 * 1) SFB_FACTOR_LAUNCH(64, 1);
     else if (a.J <= 256 * 4 * 1) SFB_FACTOR_LAUNCH(256, 1);
     else if (a.J <= 256 * 4 * 4) SFB_FACTOR_LAUNCH(256, 4);
     else if (a.J <= 256 * 4 * 12) SFB_FACTOR_LAUNCH(256, 12);
     else
-        SFB_LAUNCH((factor_u_long_kernel<MODEL>), dim3(a.n_rows), dim3(kFactorThreads), 0, s, a.zp,
-                           a.ldz, a.zstride, a.split_k, a.y, a.u, a.ldu, a.loss, a.n_rows, a.J);
+        SFB_LAUNCH((factor_u_long_kernel<MODEL, SDCA>), dim3(a.n_rows), dim3(kFactorThreads), 0, s, a.zp,
+                           a.ldz, a.zstride, a.split_k, a.y, a.u, a.ldu, a.loss, a.n_rows, a.J, a.sdca);
 #undef SFB_FACTOR_LAUNCH
     return hipGetLastError();
 }
 
 hipError_t launch_factor(const FactorArgs& a, hipStream_t s) {
+    if (a.sdca.dual != nullptr) return a.model == kMLR ? launch_factor_m<kMLR, true>(a, s) : hipErrorInvalidValue;
     switch (a.model) {
-        case kMLR: return launch_factor_m<kMLR>(a, s);
-        case kDML: return launch_factor_m<kDML>(a, s);
-        case kL2SVM: return launch_factor_m<kL2SVM>(a, s);
+        case kMLR: return launch_factor_m<kMLR, false>(a, s);
+        case kDML: return launch_factor_m<kDML, false>(a, s);
+        case kL2SVM: return launch_factor_m<kL2SVM, false>(a, s);
     }
     return hipErrorInvalidValue;
 }

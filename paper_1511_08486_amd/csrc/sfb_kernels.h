@@ -63,6 +63,18 @@ hipError_t launch_forward(const FwdArgs& a, const FwdPlan& p, hipStream_t s);
 bool forward_split_ok(const FwdArgs& a);
 hipError_t launch_forward_split(const FwdArgs& a, const FwdPlan& p, hipStream_t s);
 
+// Dual side of SDCA (Section 2.1): with `dual` set, the MLR factor kernel turns its
+// softmax residual r_i into delta u_i = frac * (u_i + r_i), stores that in U and
+// u_i - delta u_i back into row sample[i] of `dual`.
+struct SdcaDev {
+    const int32_t* sample;   // [n_rows] row of `dual` (and entry of `conj`) of every batch row
+    float* dual;             // [n_data][ldd]
+    int64_t ldd;
+    float* conj;             // [n_data] or nullptr: f_i*(-u_i) after the update
+    float frac;
+    bool vec;                // rows of `dual` are 16-byte aligned
+};
+
 struct FactorArgs {
     const float* zp;      // [split_k][n_rows][ldz]
     int64_t ldz, zstride;
@@ -73,6 +85,7 @@ struct FactorArgs {
     float* loss;          // [n_rows] or nullptr
     int n_rows, J;
     Model model;
+    SdcaDev sdca;         // dual == nullptr: plain factors
 };
 hipError_t launch_factor(const FactorArgs& a, hipStream_t s);
 

@@ -150,3 +150,35 @@ def test_ssp_and_per_sender_calls_validate_before_launching(lib):
     assert list(t) == [0, 0, 0]
     lib.sfb_ssp_destroy(ssp)
     lib.sfb_destroy(ctx)
+
+
+def test_sdca_calls_validate_before_launching(lib):
+    import paper_1511_08486_amd as sfb
+    ctx = C.c_void_p()
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 8, 16, 2, 4, sfb.SFB_F32, None) == 0
+    fake = C.c_void_p(0x1000)
+    b = sfb.binding.sfb_batch()
+    b.a, b.lda = 0x1000, 16
+
+    def sd(**kw):
+        d = sfb.binding.sfb_sdca(dual=0x1000, ld_dual=8, n_data=100, sample=0x1000, conj=None, lam=0.1, s=0.5)
+        for k, v in kw.items():
+            setattr(d, k, v)
+        return C.byref(d)
+
+    def call(d, fn=lib.sfb_sdca_compute_factors):
+        return fn(ctx, fake, 16, C.byref(b), fake, d, fake, 8, fake, 16, None)
+    assert call(None) == -1
+    assert call(sd(dual=None)) == -1 and call(sd(sample=None)) == -1 and call(sd(n_data=0)) == -1
+    assert call(sd(lam=0.0)) == -1 and call(sd(lam=float("nan"))) == -1
+    assert call(sd(s=0.0)) == -1 and call(sd(s=1.5)) == -1 and call(sd(s=float("nan"))) == -1
+    assert call(sd(ld_dual=7)) == -2
+    assert call(sd()) == -5                                   # all valid: stops at the missing workspace
+    assert call(sd(), lib.sfb_sdca_step) == -5
+    assert call(None, lib.sfb_sdca_step) == -1
+    assert call(sd(lam=1e-45, n_data=1), lib.sfb_sdca_step) == -1       # 1 / (lam n_data) overflows
+    lib.sfb_destroy(ctx)
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_DML, 8, 16, 2, 4, sfb.SFB_F32, None) == 0
+    b.a2 = 0x1000
+    assert call(sd()) == -6                                   # the dual update exists for the logistic loss only
+    lib.sfb_destroy(ctx)

@@ -196,6 +196,19 @@ def test_one_iteration_is_a_minibatch_not_a_sequence():
         a.step([1, 1], 0.4)
 
 
+def test_matrix_form_is_the_per_sample_form():
+    wl = workloads.make_sdca("sdca_tiny", seed=10, J=7, D=13, n_data=60, P=3, B=5, lam=0.02, steps=6)
+    a = SdcaMlrOracle(wl.A, wl.y, wl.J, wl.lam)
+    b = SdcaMlrOracle(wl.A, wl.y, wl.J, wl.lam)
+    for t in range(6):
+        da, fa = a.step(wl.pick(t), 0.35)
+        db, fb = b.step_matrix(wl.pick(t), 0.35)
+        np.testing.assert_allclose(db, da, rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(fb, fa, rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(b.W, a.W, rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(b.U, a.U, rtol=1e-12, atol=1e-15)
+
+
 def test_safe_fraction_is_the_single_sample_prox_sdca_step():
     """One picked sample: lam N gamma / (R^2 + lam N gamma) with gamma = 1 / smoothness."""
     assert abs(safe_fraction(0.1, 50, 1, 2.0) - 5.0 / 7.0) < 1e-15
