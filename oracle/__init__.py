@@ -7,3 +7,4 @@ bench's cpu_baseline leg have an independent definition to compare with.
 from .sfb_oracle import *  # noqa: F401,F403
 from .ssp_oracle import SspOracle  # noqa: F401
 from .sdca_oracle import SdcaMlrOracle, safe_fraction, mlr_conjugate  # noqa: F401
+from .prox_oracle import prox, PROX_KINDS  # noqa: F401
