@@ -71,6 +71,8 @@ def main():
     import numpy as np
     import torch
 
+    import __graft_entry__
+    __graft_entry__.ensure_built()        # compiles only when no library has been built yet
     import paper_1511_08486_amd as sfb
     import workloads
 

@@ -200,6 +200,28 @@ SFB_API sfb_status sfb_sdca_compute_factors(sfb_ctx *ctx, const float *W, int64_
 SFB_API sfb_status sfb_sdca_step(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_batch *batch, const int32_t *y,
                          const sfb_sdca *sdca, float *U, int64_t ldu, void *V, int64_t ldv, float *loss);
 
+/*
+ * The proximal step of proximal SGD (Section 2.1): W <- prox_{eta h}(W), in place, to be called
+ * after sfb_step / sfb_reconstruct_apply when h is not 0.  Regularisers of Section 2 with a
+ * closed form per entry or per column (the trace norm is not covered):
+ *   SFB_PROX_NONE         h = 0: nothing is launched
+ *   SFB_PROX_L2SQ         h = param/2 ||W||_F^2:        W <- W / (1 + eta param)
+ *   SFB_PROX_L1           h = param ||W||_1:            W <- sign(w) max(|w| - eta param, 0)
+ *   SFB_PROX_COLUMN_BALL  h = indicator of ||W_k||_2 <= param for every column k (sparse coding:
+ *                         dictionary columns inside the ball); W_k <- W_k min(1, param / ||W_k||_2),
+ *                         eta is ignored; needs the registered workspace.
+ * SFB_EINVAL: null W, unknown kind, eta or param negative or not finite, radius 0;
+ * SFB_ESHAPE: ldw < D; SFB_EWORKSPACE: column ball without a registered workspace.
+ * Timed under family 4 (for the column ball: the pass that forms the column norms).
+ */
+typedef enum {
+    SFB_PROX_NONE = 0,
+    SFB_PROX_L2SQ = 1,
+    SFB_PROX_L1 = 2,
+    SFB_PROX_COLUMN_BALL = 3
+} sfb_prox_kind;
+SFB_API sfb_status sfb_prox(sfb_ctx *ctx, float *W, int64_t ldw, sfb_prox_kind kind, float eta, float param);
+
 /* What the context was created with; any pointer may be NULL. */
 SFB_API sfb_status sfb_shape(const sfb_ctx *ctx, int64_t *J, int64_t *D, int32_t *P, int32_t *B,
                      int32_t *input_dtype);

@@ -2,7 +2,7 @@
 libsfb.so (hand-written HIP kernels behind a C ABI, declared in include/sfb.h).
 
 Importing this package loads the compiled library and raises ImportError if it has not
-been built (python -m paper_1511_08486_amd.build, or __graft_entry__.build()).  There
+been built (python paper_1511_08486_amd/build.py, or __graft_entry__.build()).  There
 is no CPU fallback.
 """
 from .binding import (  # noqa: F401

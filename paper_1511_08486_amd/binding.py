@@ -35,7 +35,7 @@ class sfb_sdca(C.Structure):
 def _load():
     path = library_path()
     if not os.path.exists(path):
-        raise ImportError(f"{path} is missing: build it with `python -m paper_1511_08486_amd.build` "
+        raise ImportError(f"{path} is missing: build it with `python paper_1511_08486_amd/build.py` "
                           "(there is no fallback path)")
     try:
         lib = C.CDLL(path)
@@ -66,6 +66,7 @@ def _load():
         "sfb_shape": (C.c_int, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
         "sfb_sdca_compute_factors": (C.c_int, [vp, vp, i64, pb, vp, pd, vp, i64, vp, i64, vp]),
         "sfb_sdca_step": (C.c_int, [vp, vp, i64, pb, vp, pd, vp, i64, vp, i64, vp]),
+        "sfb_prox": (C.c_int, [vp, vp, i64, C.c_int, f32, f32]),
         "sfb_ssp_create": (C.c_int, [C.POINTER(vp), vp, i32, C.POINTER(vp), i64, vp, i64, vp, i64, i32]),
         "sfb_ssp_destroy": (None, [vp]),
         "sfb_ssp_worker_step": (C.c_int, [vp, i32, pb, vp, f32, vp, C.POINTER(i32)]),
@@ -73,7 +74,11 @@ def _load():
         "sfb_ssp_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32)]),
     }
     for name, (res, args) in sigs.items():
-        fn = getattr(lib, name)          # AttributeError here = the library lacks a declared symbol
+        try:
+            fn = getattr(lib, name)
+        except AttributeError as e:
+            raise ImportError(f"{path} lacks {name}: it is older than this binding, rebuild it with "
+                              "`python paper_1511_08486_amd/build.py`") from e
         fn.restype, fn.argtypes = res, args
     return lib
 
@@ -211,6 +216,13 @@ class Sfb:
         self._check(lib.sfb_step(self._ctx, W.data_ptr(), W.stride(0), C.byref(b), y.data_ptr(), U.data_ptr(),
                                  U.stride(0), V.data_ptr(), V.stride(0), _ptr(loss), float(eta), ptr),
                     "sfb_step")
+
+    # -- proximal step ---------------------------------------------------------
+    PROX_KINDS = {"none": 0, "l2sq": 1, "l1": 2, "column_ball": 3}
+
+    def prox(self, W, kind, eta, param):
+        self._check(lib.sfb_prox(self._ctx, W.data_ptr(), W.stride(0), self.PROX_KINDS[kind], float(eta), float(param)),
+                    "sfb_prox")
 
     # -- SDCA ------------------------------------------------------------------
     @staticmethod

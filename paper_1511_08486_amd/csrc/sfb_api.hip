@@ -15,7 +15,7 @@
 using namespace sfb;
 
 namespace {
-constexpr int kFamilies = 4;  // 0 scores, 1 factor u, 2 reconstruct-apply, 3 sparse helpers
+constexpr int kFamilies = 5;  // 0 scores, 1 factor u, 2 reconstruct-apply, 3 sparse helpers, 4 proximal step
 struct EventPair { hipEvent_t a, b; };
 }  // namespace
 
@@ -71,7 +71,9 @@ size_t scores_need(const sfb_ctx* c) {
 size_t workspace_need(const sfb_ctx* c) {
     size_t need = scores_need(c);
     if (c->dtype == SFB_BF16) need += bf16_recon_workspace(c->J, c->D, (int64_t)c->P * c->B);
-    return need;
+    // the column projection of the proximal step reuses the front of the buffer between steps
+    const size_t prox = prox_workspace(c->J, c->D);
+    return need > prox ? need : prox;
 }
 
 sfb_status hip_fail(sfb_ctx* c, hipError_t e) {
@@ -385,6 +387,21 @@ sfb_status sfb_sdca_step(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* bat
     sfb_status s = sfb_sdca_compute_factors(c, W, ldw, batch, y, sdca, U, ldu, V, ldv, loss);
     if (s != SFB_OK) return s;
     return recon_launch(c, W, ldw, U, ldu, V, ldv, 1.0f, scale, nullptr);
+}
+
+sfb_status sfb_prox(sfb_ctx* c, float* W, int64_t ldw, sfb_prox_kind kind, float eta, float param) {
+    if (!c || !W) return SFB_EINVAL;
+    if ((int)kind < SFB_PROX_NONE || (int)kind > SFB_PROX_COLUMN_BALL) return SFB_EINVAL;
+    if (!std::isfinite(eta) || !std::isfinite(param) || eta < 0.f || param < 0.f) return SFB_EINVAL;
+    if (kind == SFB_PROX_COLUMN_BALL && !(param > 0.f)) return SFB_EINVAL;
+    if (ldw < c->D) return SFB_ESHAPE;
+    if (kind == SFB_PROX_NONE) return SFB_OK;
+    if (kind == SFB_PROX_COLUMN_BALL && (c->ws == nullptr || c->ws_bytes < workspace_need(c))) return SFB_EWORKSPACE;
+    ProxArgs a{W, ldw, (int)c->J, (int)c->D, (int)kind, eta, param};
+    Timed t(c, 4);
+    hipError_t e = launch_prox(a, c->ws, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e);
+    return SFB_OK;
 }
 
 sfb_status sfb_shape(const sfb_ctx* c, int64_t* J, int64_t* D, int32_t* P, int32_t* B, int32_t* input_dtype) {

@@ -106,6 +106,18 @@ hipError_t launch_csr_scores(const DensifyArgs& a, const float* W, int64_t ldw, 
 // dst[0 .. bytes) = src[0 .. bytes); both 16-byte aligned, bytes a multiple of 16.
 hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
 
+// Proximal step on W (Section 2.1).  kind: 0 identity, 1 squared l2 (param = lam), 2 l1
+// (param = lam), 3 projection of every column onto the l2 ball of radius param (needs
+// prox_workspace(J, D) bytes of 16-byte aligned device memory).
+struct ProxArgs {
+    float* w; int64_t ldw;
+    int J, D;
+    int kind;
+    float eta, param;
+};
+size_t prox_workspace(int64_t J, int64_t D);
+hipError_t launch_prox(const ProxArgs& a, void* workspace, hipStream_t s);
+
 struct ReconPlan {
     int variant;          // index into the tile table
     int bm, bn;           // W tile: rows (J) x columns (D)

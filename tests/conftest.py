@@ -10,3 +10,5 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
+    import __graft_entry__
+    __graft_entry__.ensure_built()          # compiles only when no library has been built yet

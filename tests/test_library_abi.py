@@ -182,3 +182,20 @@ def test_sdca_calls_validate_before_launching(lib):
     b.a2 = 0x1000
     assert call(sd()) == -6                                   # the dual update exists for the logistic loss only
     lib.sfb_destroy(ctx)
+
+
+def test_prox_validates_before_launching(lib):
+    import paper_1511_08486_amd as sfb
+    ctx = C.c_void_p()
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 8, 16, 2, 4, sfb.SFB_F32, None) == 0
+    fake = C.c_void_p(0x1000)
+    assert lib.sfb_prox(ctx, None, 16, 1, 0.1, 0.1) == -1
+    assert lib.sfb_prox(None, fake, 16, 1, 0.1, 0.1) == -1
+    assert lib.sfb_prox(ctx, fake, 16, 4, 0.1, 0.1) == -1 and lib.sfb_prox(ctx, fake, 16, -1, 0.1, 0.1) == -1
+    assert lib.sfb_prox(ctx, fake, 16, 1, -0.1, 0.1) == -1 and lib.sfb_prox(ctx, fake, 16, 2, 0.1, -1.0) == -1
+    assert lib.sfb_prox(ctx, fake, 16, 1, float("nan"), 0.1) == -1 and lib.sfb_prox(ctx, fake, 16, 2, 0.1, float("inf")) == -1
+    assert lib.sfb_prox(ctx, fake, 16, 3, 0.1, 0.0) == -1           # a ball of radius 0
+    assert lib.sfb_prox(ctx, fake, 15, 1, 0.1, 0.1) == -2
+    assert lib.sfb_prox(ctx, fake, 16, 3, 0.1, 1.0) == -5           # the column projection needs the workspace
+    assert lib.sfb_prox(ctx, fake, 16, 0, 0.1, 0.1) == 0            # identity: nothing is launched
+    lib.sfb_destroy(ctx)
