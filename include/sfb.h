@@ -221,6 +221,17 @@ typedef enum {
     SFB_PROX_COLUMN_BALL = 3
 } sfb_prox_kind;
 SFB_API sfb_status sfb_prox(sfb_ctx *ctx, float *W, int64_t ldw, sfb_prox_kind kind, float eta, float param);
+/* One proximal-SGD iteration (Section 2.1): sfb_reconstruct_apply / sfb_step followed by
+ * prox_{eta h}.  The entrywise kinds (squared l2, l1) are applied to every updated entry of W
+ * before the reconstruction stores it -- same result as the separate call, bit for bit, without
+ * its pass over W; the column projection runs as its own kernels after the update.
+ * Errors: those of the two calls; nothing is launched if any argument is refused. */
+SFB_API sfb_status sfb_reconstruct_apply_prox(sfb_ctx *ctx, float *W, int64_t ldw, const float *U, int64_t ldu,
+                                      const void *V, int64_t ldv, float eta, float scale,
+                                      const uint8_t *active, sfb_prox_kind kind, float param);
+SFB_API sfb_status sfb_step_prox(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_batch *batch, const int32_t *y,
+                         float *U, int64_t ldu, void *V, int64_t ldv, float *loss, float eta,
+                         const uint8_t *active, sfb_prox_kind kind, float param);
 
 /* What the context was created with; any pointer may be NULL. */
 SFB_API sfb_status sfb_shape(const sfb_ctx *ctx, int64_t *J, int64_t *D, int32_t *P, int32_t *B,

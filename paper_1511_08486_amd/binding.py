@@ -67,6 +67,8 @@ def _load():
         "sfb_sdca_compute_factors": (C.c_int, [vp, vp, i64, pb, vp, pd, vp, i64, vp, i64, vp]),
         "sfb_sdca_step": (C.c_int, [vp, vp, i64, pb, vp, pd, vp, i64, vp, i64, vp]),
         "sfb_prox": (C.c_int, [vp, vp, i64, C.c_int, f32, f32]),
+        "sfb_reconstruct_apply_prox": (C.c_int, [vp, vp, i64, vp, i64, vp, i64, f32, f32, vp, C.c_int, f32]),
+        "sfb_step_prox": (C.c_int, [vp, vp, i64, pb, vp, vp, i64, vp, i64, vp, f32, vp, C.c_int, f32]),
         "sfb_ssp_create": (C.c_int, [C.POINTER(vp), vp, i32, C.POINTER(vp), i64, vp, i64, vp, i64, i32]),
         "sfb_ssp_destroy": (None, [vp]),
         "sfb_ssp_worker_step": (C.c_int, [vp, i32, pb, vp, f32, vp, C.POINTER(i32)]),
@@ -223,6 +225,21 @@ class Sfb:
     def prox(self, W, kind, eta, param):
         self._check(lib.sfb_prox(self._ctx, W.data_ptr(), W.stride(0), self.PROX_KINDS[kind], float(eta), float(param)),
                     "sfb_prox")
+
+    def reconstruct_apply_prox(self, W, U, V, eta, kind, param, scale=None, active=None):
+        if scale is None:
+            scale = 1.0 / self.B
+        keep, ptr = self._mask(active)
+        self._check(lib.sfb_reconstruct_apply_prox(self._ctx, W.data_ptr(), W.stride(0), U.data_ptr(), U.stride(0),
+                                                   V.data_ptr(), V.stride(0), float(eta), float(scale), ptr,
+                                                   self.PROX_KINDS[kind], float(param)), "sfb_reconstruct_apply_prox")
+
+    def step_prox(self, W, batch, y, U, V, eta, kind, param, loss=None, active=None):
+        b = batch.c_struct()
+        keep, ptr = self._mask(active)
+        self._check(lib.sfb_step_prox(self._ctx, W.data_ptr(), W.stride(0), C.byref(b), y.data_ptr(), U.data_ptr(),
+                                      U.stride(0), V.data_ptr(), V.stride(0), _ptr(loss), float(eta), ptr,
+                                      self.PROX_KINDS[kind], float(param)), "sfb_step_prox")
 
     # -- SDCA ------------------------------------------------------------------
     @staticmethod

@@ -216,7 +216,8 @@ sfb_status check_recon(const sfb_ctx* c, float eta, float scale, const uint8_t* 
 
 // n_rows: factor pairs to contract over (0 = all P*B; a single worker's B otherwise, no mask)
 sfb_status recon_launch(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64_t ldu, const void* V,
-                        int64_t ldv, float eta, float scale, const uint8_t* active, int n_rows = 0) {
+                        int64_t ldv, float eta, float scale, const uint8_t* active, int n_rows = 0,
+                        int prox_kind = 0, float prox_a = 0.f) {
     ReconArgs r{};
     r.w = W; r.ldw = ldw; r.u = U; r.ldu = ldu; r.v = V; r.ldv = ldv;
     r.J = (int)c->J; r.D = (int)c->D; r.N = n_rows > 0 ? n_rows : c->P * c->B; r.B = c->B;
@@ -224,6 +225,7 @@ sfb_status recon_launch(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64
     r.bf16 = c->dtype == SFB_BF16;
     r.use_mask = false;
     r.live_mask = ~0ull;
+    r.prox_kind = prox_kind; r.prox_a = prox_a;
     if (active) {
         uint64_t m = 0;
         bool all = true;
@@ -402,6 +404,56 @@ sfb_status sfb_prox(sfb_ctx* c, float* W, int64_t ldw, sfb_prox_kind kind, float
     hipError_t e = launch_prox(a, c->ws, c->stream);
     if (e != hipSuccess) return hip_fail(c, e);
     return SFB_OK;
+}
+
+// The proximal step after an update: the entrywise kinds ride in the reconstruction's epilogue
+// (no extra pass over W), the column projection runs as its own kernels afterwards.
+static sfb_status recon_then_prox(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64_t ldu, const void* V,
+                                  int64_t ldv, float eta, float scale, const uint8_t* active, sfb_prox_kind kind,
+                                  float param) {
+    if (kind == SFB_PROX_L2SQ)
+        return recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active, 0, 1, 1.0f / (1.0f + eta * param));
+    if (kind == SFB_PROX_L1) return recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active, 0, 2, eta * param);
+    sfb_status s = recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active);
+    if (s != SFB_OK || kind == SFB_PROX_NONE) return s;
+    return sfb_prox(c, W, ldw, kind, eta, param);
+}
+
+static sfb_status check_prox(const sfb_ctx* c, sfb_prox_kind kind, float eta, float param) {
+    if ((int)kind < SFB_PROX_NONE || (int)kind > SFB_PROX_COLUMN_BALL) return SFB_EINVAL;
+    if (!std::isfinite(eta) || !std::isfinite(param) || eta < 0.f || param < 0.f) return SFB_EINVAL;
+    if (kind == SFB_PROX_COLUMN_BALL && !(param > 0.f)) return SFB_EINVAL;
+    if (kind == SFB_PROX_COLUMN_BALL && (c->ws == nullptr || c->ws_bytes < workspace_need(c))) return SFB_EWORKSPACE;
+    return SFB_OK;
+}
+
+sfb_status sfb_reconstruct_apply_prox(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64_t ldu, const void* V,
+                                      int64_t ldv, float eta, float scale, const uint8_t* active,
+                                      sfb_prox_kind kind, float param) {
+    sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
+    if (s != SFB_OK) return s;
+    s = check_recon(c, eta, scale, active);
+    if (s != SFB_OK) return s;
+    s = check_prox(c, kind, eta, param);
+    if (s != SFB_OK) return s;
+    return recon_then_prox(c, W, ldw, U, ldu, V, ldv, eta, scale, active, kind, param);
+}
+
+sfb_status sfb_step_prox(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, const int32_t* y, float* U,
+                         int64_t ldu, void* V, int64_t ldv, float* loss, float eta, const uint8_t* active,
+                         sfb_prox_kind kind, float param) {
+    sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
+    if (s != SFB_OK) return s;
+    s = check_batch(c, batch, y);
+    if (s != SFB_OK) return s;
+    const float scale = 1.0f / (float)c->B;
+    s = check_recon(c, eta, scale, active);
+    if (s != SFB_OK) return s;
+    s = check_prox(c, kind, eta, param);
+    if (s != SFB_OK) return s;
+    s = factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss);
+    if (s != SFB_OK) return s;
+    return recon_then_prox(c, W, ldw, U, ldu, V, ldv, eta, scale, active, kind, param);
 }
 
 sfb_status sfb_shape(const sfb_ctx* c, int64_t* J, int64_t* D, int32_t* P, int32_t* B, int32_t* input_dtype) {

@@ -58,7 +58,7 @@ template <bool B_FP32, int EPI, int NST, int BK, int WPS, int BM, int BN, int WG
 __global__ __launch_bounds__(WGM * WGN * 64, WPS) void nt_bf16_kernel(
     const bf16_t* __restrict__ A, int64_t lda, const void* __restrict__ Bv, int64_t ldb, float* __restrict__ C,
     int64_t ldc, int64_t cstride, bf16_t* __restrict__ Vout, int64_t ldv, int M, int N, int K, int k_slice,
-    int n_mb, int n_nb, int total, int band) {
+    int n_mb, int n_nb, int total, int band, int prox_kind, float prox_a) {
     constexpr int kBfThreads = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN, MT = WM / 32, NT = WN / 32;
     static_assert(MT >= 1 && NT >= 1 && MT * 32 * WGM == BM && NT * 32 * WGN == BN, "tile / wavefront grid mismatch");
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, WPS) void nt_bf16_kernel(
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-                    if (row < M && col < N) cout[(int64_t)row * ldc + col] = w[b][e] + acc[i][j][e];
+                    if (row < M && col < N) cout[(int64_t)row * ldc + col] = prox_entry(w[b][e] + acc[i][j][e], prox_kind, prox_a);
                 }
             }
         }
@@ -371,7 +371,7 @@ hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s) 
     if (band < 1) band = 1;
     SFB_LAUNCH((nt_bf16_kernel<false, kUpdateW, NST, BK, WPS, BM, BN, 2, 2>), dim3(total), dim3(256), lds_bytes, s, UT, ldn,
                        (const void*)VT, ldn, a.w, a.ldw, (int64_t)0, (bf16_t*)nullptr, (int64_t)0, a.J, a.D,
-                       (int)ldn, (int)ldn, n_mb, n_nb, total, band);
+                       (int)ldn, (int)ldn, n_mb, n_nb, total, band, a.prox_kind, a.prox_a);
     return hipGetLastError();
 }
 
@@ -422,7 +422,7 @@ hipError_t launch_forward_bf16(const FwdArgs& a, const FwdPlan& p, hipStream_t s
     const int total = n_mb * n_nb * p.split_k;
     SFB_LAUNCH((nt_bf16_kernel<true, kStoreZ, NST, BK, 2, BM, BN, 4, 2>), dim3(total), dim3(512), lds_bytes, s,
                        (const bf16_t*)a.a, a.lda, (const void*)a.w, a.ldw, a.zp, a.ldz, a.zstride, (bf16_t*)a.v,
-                       a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_mb, n_nb, total, 1);
+                       a.ldv, a.n_rows, a.J, a.D, p.k_slice, n_mb, n_nb, total, 1, 0, 0.f);
     return hipGetLastError();
 }
 

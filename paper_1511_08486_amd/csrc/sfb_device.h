@@ -124,6 +124,19 @@ template <> __device__ __forceinline__ uint2 to_raw<bf16_t>(f32x4 v) {
     return q;
 }
 
+// Entrywise proximal operator (Section 2.1), applied to an updated entry of W before it is
+// stored: kind 0 none, 1 w * a (squared l2: a = 1 / (1 + eta lam)), 2 soft threshold at
+// a = eta lam (l1).  `kind` is uniform over the launch.
+__device__ __forceinline__ float prox_entry(float w, int kind, float a) {
+    if (kind == 1) return w * a;
+    if (kind == 2) return w > a ? w - a : (w < -a ? w + a : 0.f);
+    return w;
+}
+__device__ __forceinline__ f32x4 prox_entry4(f32x4 w, int kind, float a) {
+    if (kind == 0) return w;
+    return f32x4{prox_entry(w.x, kind, a), prox_entry(w.y, kind, a), prox_entry(w.z, kind, a), prox_entry(w.w, kind, a)};
+}
+
 __device__ __forceinline__ void store4(float* __restrict__ row, int64_t col, int64_t ncols, bool vec, f32x4 v) {
     if (vec && col + 3 < ncols) {
         *reinterpret_cast<f32x4*>(row + col) = v;

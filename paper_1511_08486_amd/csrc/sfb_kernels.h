@@ -136,6 +136,8 @@ struct ReconArgs {
     float alpha;                   // -eta * scale
     uint64_t live_mask;            // bit p = worker p contributes
     bool use_mask, bf16;
+    int prox_kind = 0;             // entrywise proximal operator applied to the updated entries
+    float prox_a = 0.f;            //   before they are stored: see prox_entry (0 = none)
 };
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s);
 // fp32 reconstruction as six bf16 term products per product (sfb_reconstruct_split.hip); 128 x 128 tiles

@@ -66,9 +66,7 @@ __global__ __launch_bounds__(kProxThreads) void prox_entry_kernel(float* __restr
         for (int i = 0; i < UN; ++i) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float w = v[i][e];
-                if (KIND == 1) v[i][e] = w * a;
-                else v[i][e] = w > a ? w - a : (w < -a ? w + a : 0.f);
+                v[i][e] = prox_entry(v[i][e], KIND, a);
             }
             if (r + i < r1) store4(W + (int64_t)(r + i) * ldw, col, D, vec, v[i]);
         }

@@ -45,7 +45,7 @@ template <int MT, int NWR, int KS, typename TV, bool FAST, bool MASK>
 __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
     float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const TV* __restrict__ V,
     int64_t ldv, int J, int D, int N, int B, float alpha, uint64_t live_mask, int n_jb, int total, bool vec_w,
-    bool vec_u, bool vec_v) {
+    bool vec_u, bool vec_v, int prox_kind, float prox_a) {
     constexpr int BK = kReconBK, BN = kReconBN, G = kReconGroup;
     constexpr int WMR = 32 * MT;            // rows per wavefront
     constexpr int BM = WMR * NWR;
@@ -275,6 +275,7 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
                     w.y += acc[t][1][K * EH + x];
                     w.z += acc[t][2][K * EH + x];
                     w.w += acc[t][3][K * EH + x];
+                    w = prox_entry4(w, prox_kind, prox_a);
                     if (FAST) *reinterpret_cast<f32x4*>(W + (int64_t)row * ldw + d0 + 4 * l32) = w;
                     else store4(W + (int64_t)row * ldw, d0 + 4 * l32, D, vec_w, w);
                 }
@@ -304,7 +305,7 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
 template <int MT, int NWR, int BK, int NST>
 __global__ __launch_bounds__(NWR * 64, 1) void reconstruct_apply_dma_kernel(
     float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const float* __restrict__ V,
-    int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total) {
+    int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total, int prox_kind, float prox_a) {
     constexpr int BN = kReconBN, G = kReconGroup;
     constexpr int WMR = 32 * MT;
     constexpr int BM = WMR * NWR;
@@ -497,6 +498,7 @@ __global__ __launch_bounds__(NWR * 64, 1) void reconstruct_apply_dma_kernel(
                 w.y += alpha * acc[t][1][e];
                 w.z += alpha * acc[t][2][e];
                 w.w += alpha * acc[t][3][e];
+                w = prox_entry4(w, prox_kind, prox_a);
                 *reinterpret_cast<f32x4*>(W + (int64_t)row * ldw + d0 + 4 * l32) = w;
             }
         }
@@ -516,7 +518,8 @@ static hipError_t launch_recon_dma(const ReconArgs& a, hipStream_t s) {
         raised = true;
     }
     SFB_LAUNCH((reconstruct_apply_dma_kernel<MT, NWR, BK, NST>), dim3(total), dim3(NWR * 64), lds_bytes, s, a.w,
-                       a.ldw, a.u, a.ldu, (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total);
+                       a.ldw, a.u, a.ldu, (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total, a.prox_kind,
+                       a.prox_a);
     return hipGetLastError();
 }
 
@@ -589,7 +592,7 @@ static hipError_t launch_recon_f(const ReconArgs& a, hipStream_t s, bool vec_w, 
     }
     SFB_LAUNCH((reconstruct_apply_kernel<MT, NWR, KS, TV, FAST, MASK>), dim3(total),
                        dim3(NWR * KS * 64), lds_bytes, s, a.w, a.ldw, a.u, a.ldu, (const TV*)a.v, a.ldv, a.J, a.D,
-                       a.N, a.B, a.alpha, a.live_mask, n_jb, total, vec_w, vec_u, vec_v);
+                       a.N, a.B, a.alpha, a.live_mask, n_jb, total, vec_w, vec_u, vec_v, a.prox_kind, a.prox_a);
     return hipGetLastError();
 }
 

@@ -33,7 +33,7 @@ __device__ __forceinline__ void rs_barrier() {
 
 __global__ __launch_bounds__(kRsThreads, 2) void reconstruct_split_kernel(
     float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const float* __restrict__ V,
-    int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total) {
+    int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total, int prox_kind, float prox_a) {
     constexpr int BM = kRsBM, BN = kRsBN, BK = kRsBK, ROWB = kRsRowB;
     constexpr int WGN = 2, WM = 32, WN = 64, NT = 2;
     extern __shared__ __attribute__((aligned(16))) unsigned char rs_lds[];
@@ -168,7 +168,8 @@ __global__ __launch_bounds__(kRsThreads, 2) void reconstruct_split_kernel(
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int row = j0 + wm * WM + 8 * (e / 4) + 4 * half + (e % 4);
-            if (row < J && col < D) W[(int64_t)row * ldw + col] = wreg[t][e] + alpha * (lead[t][e] + corr[t][e]);
+            if (row < J && col < D) W[(int64_t)row * ldw + col] =
+                    prox_entry(wreg[t][e] + alpha * (lead[t][e] + corr[t][e]), prox_kind, prox_a);
         }
     }
 }
@@ -191,7 +192,7 @@ hipError_t launch_reconstruct_split(const ReconArgs& a, hipStream_t s) {
     const int n_jb = (a.J + kRsBM - 1) / kRsBM, n_db = (a.D + kRsBN - 1) / kRsBN;
     const int total = n_jb * n_db;
     SFB_LAUNCH(reconstruct_split_kernel, dim3(total), dim3(kRsThreads), lds_bytes, s, a.w, a.ldw, a.u, a.ldu,
-               (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total);
+               (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total, a.prox_kind, a.prox_a);
     return hipGetLastError();
 }
 

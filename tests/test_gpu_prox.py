@@ -115,3 +115,45 @@ def test_full_size_columns_sampled(sfb):
     norms = torch.linalg.vector_norm(W.double(), dim=0)
     assert float(norms.max()) <= 1.0 + 1e-5
     ctx.close()
+
+
+FUSED_CASES = [
+    ("mlr_medium", {}, None),                                            # LDS-DMA fp32 kernels
+    ("mlr_tiny", dict(J=37, D=203, P=3, B=5), None),                     # register-staged fp32 kernel, ragged
+    ("mlr_medium", dict(J=520, D=1024, P=4, B=48), dict(fwd_dma=13)),    # split-bf16 contractions
+    ("mlr_large", dict(J=300, D=1024, P=4, B=40), None),                 # bf16 features: bf16 matrix-core kernels
+    ("dml", dict(J=72, D=256, P=2, B=32), None),
+    ("l2svm", dict(J=64, D=512, P=2, B=16, density=0.05), None),
+]
+
+
+@pytest.mark.parametrize("name,override,plan", FUSED_CASES)
+@pytest.mark.parametrize("kind,param", [("l2sq", 0.05), ("l1", 2e-3), ("column_ball", 1.2), ("none", 0.0)])
+def test_step_prox_is_step_then_prox_bit_for_bit_and_matches_the_oracle(sfb, name, override, plan, kind, param):
+    wl = workloads.make(name, seed=7, **override)
+    tol = 2e-2 if wl.dtype == "bf16" else 1e-4
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=DEV)
+    if plan:
+        ctx.set_plan(**plan)
+    Wa, Wb = device_w(wl.W0, 0), device_w(wl.W0, 0)
+    U, V, loss = alloc_factors(wl, DEV)
+    Wo = wl.W0.astype(np.float64)
+    for t in range(3):
+        db, dy = to_device(wl, wl.batch(t), DEV)
+        active = [1, 0] + [1] * (wl.P - 2) if (t == 1 and wl.P >= 2) else None      # one dead worker once
+        ctx.step_prox(Wa, db, dy, U, V, wl.eta, kind, param, active=active)
+        ctx.step(Wb, db, dy, U, V, wl.eta, active=active)
+        ctx.prox(Wb, kind, wl.eta, param)
+        ctx.sync()
+        assert torch.equal(Wa, Wb), f"step {t}: fused and separate proximal steps differ"
+        _, _, Wo, _ = oracle.step(wl.model, Wo, wl.batch(t), wl.P, wl.B, wl.eta, active=active)
+        Wo = prox(kind, Wo, wl.eta, param)
+        assert_close(Wa.cpu().numpy(), Wo, tol, f"W after step {t} + {kind}")
+    # the two-call form of the same iteration
+    db, dy = to_device(wl, wl.batch(3), DEV)
+    ctx.compute_factors(Wa, db, dy, U, V)
+    ctx.reconstruct_apply_prox(Wa, U, V, wl.eta, kind, param)
+    ctx.step_prox(Wb, db, dy, U, V, wl.eta, kind, param)
+    ctx.sync()
+    assert torch.equal(Wa, Wb)
+    ctx.close()

@@ -198,4 +198,14 @@ def test_prox_validates_before_launching(lib):
     assert lib.sfb_prox(ctx, fake, 15, 1, 0.1, 0.1) == -2
     assert lib.sfb_prox(ctx, fake, 16, 3, 0.1, 1.0) == -5           # the column projection needs the workspace
     assert lib.sfb_prox(ctx, fake, 16, 0, 0.1, 0.1) == 0            # identity: nothing is launched
+    # the fused forms refuse the same things, before anything is launched
+    b = sfb.binding.sfb_batch()
+    b.a, b.lda = 0x1000, 16
+    assert lib.sfb_reconstruct_apply_prox(ctx, fake, 16, fake, 8, fake, 16, 0.1, 1.0, None, 7, 0.1) == -1
+    assert lib.sfb_reconstruct_apply_prox(ctx, fake, 16, fake, 8, fake, 16, 0.1, 1.0, None, 2, -0.1) == -1
+    assert lib.sfb_reconstruct_apply_prox(ctx, fake, 16, fake, 8, fake, 16, 0.1, 1.0, None, 3, 1.0) == -5
+    assert lib.sfb_reconstruct_apply_prox(ctx, None, 16, fake, 8, fake, 16, 0.1, 1.0, None, 1, 0.1) == -1
+    assert lib.sfb_step_prox(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None, 0.1, None, 9, 0.1) == -1
+    assert lib.sfb_step_prox(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None, 0.1, None, 3, 0.0) == -1
+    assert lib.sfb_step_prox(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None, 0.1, None, 1, 0.1) == -5
     lib.sfb_destroy(ctx)
