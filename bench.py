@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--objective-every", type=int, default=0,
                     help="after the timed run, replay the steps from W0 (untimed) and report the mean per-sample "
                          "loss of the batch of every K-th step against samples processed")
+    ap.add_argument("--prox", default="",
+                    help="KIND:PARAM (l2sq, l1 or column_ball): after the timed run, also time proximal-SGD "
+                         "iterations (the step followed by prox_{eta h}), fused and as two calls; informational")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -244,6 +247,32 @@ def main():
                            "unit": "samples/s", "ms_per_step": el / args.steps * 1e3,
                            "note": "fp32 operands split exactly into three bf16 terms, six term products per product"}
         alt.close()
+    if args.prox:
+        # informational: proximal SGD (Section 2.1), the step followed by the proximal operator of h
+        kind, param = args.prox.split(":")
+        param = float(param)
+
+        def timed(fn):
+            W.copy_(W0)
+            for t in range(args.warmup):
+                fn(*pool[t % len(pool)])
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for t in range(args.steps):
+                fn(*pool[t % len(pool)])
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t1) / args.steps * 1e3
+
+        def two_calls(b, y):
+            ctx.step(W, b, y, U, V, wl.eta)
+            ctx.prox(W, kind, wl.eta, param)
+
+        out["proximal_step"] = {
+            "h": f"{kind} (parameter {param})",
+            "ms_per_step_one_call": timed(lambda b, y: ctx.step_prox(W, b, y, U, V, wl.eta, kind, param)),
+            "ms_per_step_two_calls": timed(two_calls),
+            "note": "sfb_step_prox folds the entrywise operators into the reconstruction's store; the column "
+                    "projection runs as its own kernels either way"}
     if args.objective_every > 0:
         # objective vs samples on the synthetic data (Section 6's third panel), from the loss the factor kernel emits
         W.copy_(W0)
