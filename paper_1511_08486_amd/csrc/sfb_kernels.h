@@ -140,6 +140,11 @@ struct ReconArgs {
     float prox_a = 0.f;            //   before they are stored: see prox_entry (0 = none)
 };
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s);
+// 64 x 64 tiles, one 32 x 32 block per wavefront (sfb_reconstruct_small.hip): for shapes whose
+// block count leaves the larger tiles' busiest SIMD with clearly more work than the average
+bool reconstruct_small_ok(const ReconArgs& a);
+bool reconstruct_small_wins(int64_t J, int64_t D, int big_bm, int big_waves);
+hipError_t launch_reconstruct_small(const ReconArgs& a, hipStream_t s);
 // fp32 reconstruction as six bf16 term products per product (sfb_reconstruct_split.hip); 128 x 128 tiles
 bool reconstruct_split_ok(const ReconArgs& a);
 hipError_t launch_reconstruct_split(const ReconArgs& a, hipStream_t s);

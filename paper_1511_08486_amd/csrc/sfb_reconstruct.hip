@@ -541,7 +541,9 @@ static const ReconVariant kReconVariants[] = {
     {2, 2, 2, false},  // 6: 128 x 128, 4 wavefronts of 64 rows
     {1, 4, 1, true},   // 7: 128 x 128, 4 wavefronts, LDS-DMA staging (falls back to 0)
     {1, 2, 1, true},   // 8: 64 x 128, 2 wavefronts, LDS-DMA staging (falls back to 1)
+    {1, 2, 1, true},   // 9: 64 x 64, 4 wavefronts of one 32 x 32 block each, LDS-DMA staging (falls back to 8)
 };
+constexpr int kSmallVariant = 9;
 constexpr int kNumReconVariants = sizeof(kReconVariants) / sizeof(kReconVariants[0]);
 
 int num_reconstruct_variants() { return kNumReconVariants; }
@@ -565,6 +567,12 @@ ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
         // wavefronts multiply clamped rows that are never stored)
         variant = J > 64 ? 8 : 7;
     }
+    // single-block wavefronts where the lumps of four blocks would leave the busiest SIMD with
+    // clearly more than its share (e.g. J = 600: 3 blocks instead of 4)
+    if (kReconVariants[variant].dma) {
+        const int bm = 32 * kReconVariants[variant].mt * kReconVariants[variant].nwr;
+        if (reconstruct_small_wins(J, D, bm, kReconVariants[variant].nwr)) variant = kSmallVariant;
+    }
     return plan_reconstruct_variant(J, D, variant);
 }
 
@@ -572,7 +580,7 @@ ReconPlan plan_reconstruct_variant(int64_t J, int64_t D, int variant) {
     ReconPlan p;
     p.variant = variant;
     p.bm = 32 * kReconVariants[variant].mt * kReconVariants[variant].nwr;
-    p.bn = kReconBN;
+    p.bn = variant == kSmallVariant ? 64 : kReconBN;
     p.grid = (int)(((J + p.bm - 1) / p.bm) * ((D + p.bn - 1) / p.bn));
     return p;
 }
@@ -625,14 +633,18 @@ static hipError_t launch_recon_v(const ReconArgs& a, const ReconPlan& p, hipStre
 
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s) {
     ReconPlan q = p;
-    if (kReconVariants[p.variant].dma) {
+    if (p.variant == kSmallVariant) {
+        if (reconstruct_small_ok(a)) return launch_reconstruct_small(a, s);
+        q.variant = 8;
+    }
+    if (kReconVariants[q.variant].dma) {
         if (dma_ok(a, kReconBK)) {
-            switch (p.variant) {
+            switch (q.variant) {
                 case 7: return launch_recon_dma<1, 4, kReconBK, 3>(a, s);
                 case 8: return launch_recon_dma<1, 2, kReconBK, 3>(a, s);
             }
         }
-        q.variant = p.variant == 8 ? 1 : 0;   // same tile, register staging
+        q.variant = q.variant == 8 ? 1 : 0;   // same tile, register staging
     }
     return a.bf16 ? launch_recon_v<bf16_t>(a, q, s) : launch_recon_v<float>(a, q, s);
 }

@@ -1,0 +1,166 @@
+// Reconstruction + update (Section 3, Section 2.1), fine-grained form:
+//     W[j][d] <- W[j][d] + alpha * sum_n U[n][j] * V[n][d]
+// with 64 x 64 tiles of W and ONE 32 x 32 MFMA block per wavefront.
+//
+// Why a second tile shape.  The unit of matrix-core work is a 32 x 32 block of W carried
+// through all N factor pairs, and a launch is as slow as its busiest SIMD.  With the 32 x 128
+// wavefront tiles of the other kernels a SIMD gets work in lumps of four blocks: J = 600,
+// D = 4096 is 2432 blocks for 1024 SIMDs, 2.4 each on average, but 4 for the busiest.  Handing
+// out single blocks (2560 wavefronts, two or three per SIMD) makes that 3 (measured: the time
+// per factor pair drops from 4.0 to 3.5 block times, J = 600: 71 -> 64 us).  The price is less
+// operand reuse: every MFMA needs its own two LDS words, and a 64 x 64 tile fetches twice the
+// factor bytes per flop of a 128 x 128 one -- affordable, the factors sit in L2.  The host
+// picks this kernel only where the block count says it wins.
+//
+// Staging is the LDS-DMA ring of the larger kernel: factor tiles [k][64] go from L2 straight
+// into LDS (lds_dma16), three stages, completion tracked by hand with the in-order
+// vector-memory counter; the W block is requested after the first stage (ordinary loads) and
+// consumed in the epilogue.  alpha and the entrywise proximal operator are applied there.
+#include "sfb_device.h"
+#include "sfb_kernels.h"
+
+namespace sfb {
+
+constexpr int kRsmBM = 64, kRsmBN = 64, kRsmBK = 32, kRsmStages = 3, kRsmThreads = 256;
+
+__global__ __launch_bounds__(kRsmThreads) void reconstruct_apply_small_kernel(
+    float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const float* __restrict__ V,
+    int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total, int prox_kind, float prox_a) {
+    constexpr int BM = kRsmBM, BN = kRsmBN, BK = kRsmBK, NST = kRsmStages, THREADS = kRsmThreads;
+    constexpr int U_LD = BK * BM / 4 / THREADS, V_LD = BK * BN / 4 / THREADS;      // 16-byte DMAs per thread and stage
+    constexpr int DMAS = U_LD + V_LD;
+    constexpr int STAGE_FLOATS = BK * (BM + BN);
+    constexpr int W_LOADS = 16;
+    static_assert(U_LD == 2 && V_LD == 2, "tile / thread count mismatch");
+    static_assert(NST == 3, "ring depth");
+    static_assert(DMAS + W_LOADS <= 63, "wait count encoding");
+    __shared__ __attribute__((aligned(16))) float lds[NST * STAGE_FLOATS];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wr = wave >> 1, wc = wave & 1;                // this wavefront's 32 x 32 block of the tile
+    const int id = xcd_contiguous_id(blockIdx.x, total);
+    const int jb = id % n_jb, db = id / n_jb;
+    const int j0 = jb * BM, d0 = db * BN;
+
+    // source of DMA i of a stage: item idx = tid + i * THREADS, row idx / 16 of the chunk,
+    // 16-byte item idx % 16 of the 64-float row.  Columns of U beyond J are clamped (host:
+    // J % 4 == 0, J >= 4): they feed rows of W that are never stored.
+    const float* pu[U_LD];
+    const float* pv[V_LD];
+#pragma unroll
+    for (int i = 0; i < U_LD; ++i) {
+        const int idx = tid + i * THREADS;
+        pu[i] = U + (int64_t)(idx / (BM / 4)) * ldu + min(j0 + (idx % (BM / 4)) * 4, J - 4);
+    }
+#pragma unroll
+    for (int i = 0; i < V_LD; ++i) {
+        const int idx = tid + i * THREADS;
+        pv[i] = V + (int64_t)(idx / (BN / 4)) * ldv + d0 + (idx % (BN / 4)) * 4;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    const int64_t ustep = (int64_t)BK * ldu, vstep = (int64_t)BK * ldv;
+    auto issue = [&](int chunk, int st) {
+        const uint32_t ubase = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(st * STAGE_FLOATS + wave * 64 * 4) * 4u);
+        const uint32_t vbase = ubase + (uint32_t)(BK * BM) * 4u;
+#pragma unroll
+        for (int i = 0; i < U_LD; ++i) lds_dma16(pu[i] + chunk * ustep, ubase + (uint32_t)(i * THREADS * 16));
+#pragma unroll
+        for (int i = 0; i < V_LD; ++i) lds_dma16(pv[i] + chunk * vstep, vbase + (uint32_t)(i * THREADS * 16));
+    };
+
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+
+    // MFMA k-step kk covers pairs 2 kk and 2 kk + 1 of the chunk: lanes 0-31 carry the first
+    // (row / column l32), lanes 32-63 the second.  All 32 operand words of a chunk are read
+    // before its first MFMA, so that no MFMA but the first waits on LDS.
+    auto compute = [&](int st) {
+        const float* us = &lds[st * STAGE_FLOATS + wr * 32 + l32 + half * BM];
+        const float* vs = &lds[st * STAGE_FLOATS + BK * BM + wc * 32 + l32 + half * BN];
+        constexpr int KS = BK / 2;
+        float a[KS], b[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            a[s] = us[2 * s * BM];
+            b[s] = vs[2 * s * BN];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], b[s], acc, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    const int n_chunks = N / BK;   // host: N % BK == 0, N >= BK
+    issue(0, 0);
+    if (1 < n_chunks) issue(1, 1);
+
+    // step c: my DMAs of chunk c have landed once at most `allowed` younger operations are
+    // outstanding; the barrier makes everybody's visible and says that stage (c - 1) % 3 is
+    // free again, which the DMAs of chunk c + 2 then refill
+    auto step = [&](int c, int st, int allowed) {
+        if (allowed >= DMAS + W_LOADS) wait_vmcnt<DMAS + W_LOADS>();
+        else if (allowed >= W_LOADS) wait_vmcnt<W_LOADS>();
+        else if (allowed >= DMAS) wait_vmcnt<DMAS>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (c + 2 < n_chunks) issue(c + 2, st == 0 ? 2 : st - 1);
+        compute(st);
+    };
+
+    step(0, 0, 1 < n_chunks ? DMAS : 0);
+    // W block after the first stage: nothing competes with chunk 0 for the first MFMA, and the
+    // loads have the rest of the contraction to arrive.  In counter order they sit between the
+    // DMAs of chunk 2 and those of chunk 3: while chunks 1 and 2 are waited for they count as
+    // younger operations, from chunk 3 on they are older and have retired.
+    float wreg[16];
+    const int col = d0 + wc * 32 + l32;                     // host: D % 64 == 0, so col < D
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int row = j0 + wr * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+        wreg[e] = W[(int64_t)min(row, J - 1) * ldw + col];
+    }
+    int st = 1;
+    for (int c = 1; c < n_chunks; ++c) {
+        step(c, st, (c + 1 < n_chunks ? DMAS : 0) + (c <= 2 ? W_LOADS : 0));
+        st = st == 2 ? 0 : st + 1;
+    }
+
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int row = j0 + wr * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+        if (row < J) W[(int64_t)row * ldw + col] = prox_entry(wreg[e] + alpha * acc[e], prox_kind, prox_a);
+    }
+}
+
+bool reconstruct_small_ok(const ReconArgs& a) {
+    auto al = [](const void* p, int64_t ld) { return ((uintptr_t)p % 16) == 0 && (ld % 4) == 0; };
+    return !a.bf16 && !a.use_mask && al(a.u, a.ldu) && al(a.v, a.ldv) && (a.D % kRsmBN) == 0 && (a.J % 4) == 0 &&
+           a.J >= 4 && (a.N % kRsmBK) == 0 && a.N >= kRsmBK;
+}
+
+// 32 x 32 blocks the busiest SIMD carries when the work is handed out as `waves` wavefronts
+// of `blocks_per_wave` blocks each (1024 SIMDs; the dispatcher spreads wavefronts evenly).
+static int64_t busiest_simd_blocks(int64_t waves, int blocks_per_wave) {
+    return (waves + 1023) / 1024 * blocks_per_wave;
+}
+
+// True when single-block wavefronts finish clearly sooner than the given larger tile would.
+bool reconstruct_small_wins(int64_t J, int64_t D, int big_bm, int big_waves) {
+    if ((D % kRsmBN) != 0) return false;
+    const int64_t small_waves = ((J + kRsmBM - 1) / kRsmBM) * (D / kRsmBN) * 4;
+    const int64_t big_tiles = ((J + big_bm - 1) / big_bm) * ((D + 127) / 128);
+    const int blocks_per_big_wave = (big_bm / big_waves) / 32 * 4;
+    return 10 * busiest_simd_blocks(small_waves, 1) <= 8 * busiest_simd_blocks(big_tiles * big_waves, blocks_per_big_wave);
+}
+
+hipError_t launch_reconstruct_small(const ReconArgs& a, hipStream_t s) {
+    const int n_jb = (a.J + kRsmBM - 1) / kRsmBM, n_db = a.D / kRsmBN;
+    const int total = n_jb * n_db;
+    SFB_LAUNCH(reconstruct_apply_small_kernel, dim3(total), dim3(kRsmThreads), 0, s, a.w, a.ldw, a.u, a.ldu,
+               (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total, a.prox_kind, a.prox_a);
+    return hipGetLastError();
+}
+
+}  // namespace sfb

@@ -69,6 +69,28 @@ def test_lds_dma_reconstruct_variants(sfb, variant, J, D, P, B):
     run_chain(wl, 3, TOL32, plan=dict(recon_variant=variant))
 
 
+@pytest.mark.parametrize("J,D,P,B", [(600, 4096, 8, 128), (520, 1024, 4, 48), (36, 256, 1, 32), (64, 64, 2, 32),
+                                     (100, 192, 3, 32), (4, 64, 1, 128), (1000, 4096, 8, 64)])
+def test_single_block_reconstruct_variant(sfb, J, D, P, B):
+    """Variant 9 (64 x 64 tiles, one 32 x 32 block per wavefront; D % 64 == 0, J % 4 == 0, N % 32 == 0):
+    ring of one to many stages (N = 32 ... 1024), ragged last row tile, a single tile."""
+    wl = workloads.make("mlr_medium", seed=9, J=J, D=D, P=P, B=B, steps=3, pool=2)
+    run_chain(wl, 3, TOL32, plan=dict(recon_variant=9))
+
+
+def test_single_block_variant_is_what_the_plan_picks_for_600_rows_and_falls_back_when_it_must(sfb):
+    import paper_1511_08486_amd as m
+    ctx = m.Sfb("dml", 600, 4096, 8, 128, device="cuda:0")
+    assert ctx.plan_info()["recon_grid"] == 10 * 64          # 64 x 64 tiles
+    ctx.close()
+    ctx = m.Sfb("mlr", 1000, 4096, 8, 64, device="cuda:0")
+    assert ctx.plan_info()["recon_grid"] == 256              # a tie in the block count keeps the 128 x 128 tiles
+    ctx.close()
+    # shapes the kernel does not take (D % 64 != 0, N % 32 != 0, a dead worker) run the other kernels
+    wl = workloads.make("mlr_medium", seed=10, J=72, D=200, P=3, B=20, steps=2, pool=2)
+    run_chain(wl, 2, TOL32, plan=dict(recon_variant=9))
+
+
 def test_dml_twenty_steps(sfb):
     wl = workloads.make("dml", seed=1)    # seed 1 keeps every pair > 1e-4 from the hinge kink
     worst = run_chain(wl, wl.steps, TOL32, check_every=3)
