@@ -356,50 +356,55 @@ def test_split_bf16_scores_are_as_accurate_as_fp32_mfma(sfb):
     assert errs[5][0] <= 2.0 * errs[1][0] + 1e-9 and errs[5][1] <= 2.0 * errs[1][1] + 1e-7
 
 
-def test_w_with_more_than_2_to_31_entries(sfb):
+@pytest.mark.parametrize("dtype,P,B", [("f32", 1, 32), ("bf16", 4, 32)])
+def test_w_with_more_than_2_to_31_entries(sfb, dtype, P, B):
     """J * D = 34000 * 65536 = 2.2e9 entries (8.9 GB): every kernel's addressing past 2^31 elements.
     W is the fp32 outer product of two vectors, so the oracle can form any block of it without holding
     it; the scores, U and the loss are compared in full, the updated W on sampled rows (first, last,
     and around the 2^31-th element) and columns."""
     import paper_1511_08486_amd as m
-    J, D, P, B = 34000, 65536, 1, 32
+    J, D, N = 34000, 65536, P * B
+    tol = TOL32 if dtype == "f32" else 2e-2
+    vdt = torch.float32 if dtype == "f32" else torch.bfloat16
     rng = np.random.default_rng(11)
     a = (0.1 * rng.standard_normal(J)).astype(np.float32)
     b = rng.standard_normal(D).astype(np.float32)
-    A = (rng.standard_normal((B, D)) / np.sqrt(D)).astype(np.float32)
-    y = rng.integers(0, J, size=B).astype(np.int32)
+    A = (rng.standard_normal((N, D)) / np.sqrt(D)).astype(np.float32)
+    if dtype == "bf16":
+        A = workloads.bf16_round(A)[1]
+    y = rng.integers(0, J, size=N).astype(np.int32)
     dev = "cuda:0"
     W = torch.outer(torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev))          # fl32(a_j * b_d)
-    ctx = m.Sfb("mlr", J, D, P, B, device=dev)
-    U = torch.empty((B, J), dtype=torch.float32, device=dev)
-    V = torch.empty((B, D), dtype=torch.float32, device=dev)
-    loss = torch.empty((B,), dtype=torch.float32, device=dev)
+    ctx = m.Sfb("mlr", J, D, P, B, dtype=dtype, device=dev)
+    U = torch.empty((N, J), dtype=torch.float32, device=dev)
+    V = torch.empty((N, D), dtype=vdt, device=dev)
+    loss = torch.empty((N,), dtype=torch.float32, device=dev)
     eta = 0.5
-    ctx.step(W, m.SfbBatch(a=torch.from_numpy(A).to(dev)), torch.from_numpy(y).to(dev), U, V, eta, loss=loss)
+    ctx.step(W, m.SfbBatch(a=torch.from_numpy(A).to(vdt).to(dev)), torch.from_numpy(y).to(dev), U, V, eta, loss=loss)
     ctx.sync()
 
     def w_block(rows, cols):                    # the same fp32 products, widened
         return (a[rows, None] * b[None, cols]).astype(np.float64)
     A64 = A.astype(np.float64)
-    Z = np.empty((B, J))
+    Z = np.empty((N, J))
     for r0 in range(0, J, 2000):
         rows = np.arange(r0, min(J, r0 + 2000))
         Z[:, rows] = A64 @ w_block(rows, np.arange(D)).T
     want_loss, Uo = oracle.loss_and_u("mlr", Z, y)                  # the oracle's pinned factor step
-    assert_close(U.cpu().numpy(), Uo, TOL32, "U")
-    assert_close(loss.cpu().numpy(), want_loss, TOL32, "loss")
-    assert torch.equal(V.cpu(), torch.from_numpy(A))
+    assert_close(U.cpu().numpy(), Uo, tol, "U")
+    assert_close(loss.cpu().numpy(), want_loss, tol, "loss")
+    assert torch.equal(V.float().cpu(), torch.from_numpy(A))
     edge = (1 << 31) // D                                           # the row holding the 2^31-th element
     rows = np.unique(np.concatenate([np.arange(0, 3), np.arange(edge - 2, edge + 3), np.arange(J - 3, J),
                                      rng.integers(0, J, size=40), y[:4]]))
     cols = np.unique(np.concatenate([np.arange(0, 4), np.arange(D - 4, D), rng.integers(0, D, size=120)]))
     want_w = oracle.apply_update(w_block(rows, cols), oracle.delta_w(Uo[:, rows], A64[:, cols], P, B), eta)
     got_w = W[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
-    assert_close(got_w, want_w, TOL32, "sampled W")
+    assert_close(got_w, want_w, tol, "sampled W")
     # the update really happened on those entries
     assert np.abs(want_w - w_block(rows, cols)).max() > 1e-4
     ctx.prox(W, "l2sq", 0.5, 1.0)                                   # streaming kernels past 2^31 elements too
     ctx.sync()
     got_p = W[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
-    assert_close(got_p, oracle.prox("l2sq", want_w, 0.5, 1.0), TOL32, "sampled W after the proximal step")
+    assert_close(got_p, oracle.prox("l2sq", want_w, 0.5, 1.0), tol, "sampled W after the proximal step")
     ctx.close()
