@@ -27,6 +27,18 @@ tau is a COUNT of applied updates (the inner sum of the printed rule runs
 partial update is a constant that rescales eta and is left to the caller, so that
 staleness 0 reproduces the bulk-synchronous step of sfb_oracle exactly.
 
+Partial broadcast (Section 4.3, Halton sequence broadcast): a worker sends its factors to
+Q peers only, worker p to (p + floor(P h)) mod P for the first Q terms h of the sequence
+1/2, 1/4, 3/4, 1/8, 3/8, ... (the order the paper prints: level by level, odd numerators
+ascending -- not the bit-reversed order of the textbook base-2 Halton sequence, whose fifth
+term would be 5/8; offsets that are 0 or repeat an earlier one are skipped).  ``receivers[q]``
+is the set of workers q sends to.  Reading: the staleness rule then ranges over the workers
+that send to p (nothing else can ever arrive), a delivery along a missing edge is illegal,
+and the replicas no longer agree once everything has arrived (the paper: per-iteration
+consistency is lost).  ``queue`` bounds how many of its own factor sets a sender may hold
+that some receiver has not applied yet (the output queue of Section 4.4 made finite); with
+full broadcast and queue >= 2 s + 2 it never binds.
+
 Every replica is formed from the stored factors by the sum above each time it is
 asked for; nothing is accumulated incrementally.
 """
@@ -36,15 +48,41 @@ import numpy as np
 
 from . import sfb_oracle as _o
 
-__all__ = ["SspOracle"]
+__all__ = ["SspOracle", "halton_offsets", "halton_receivers"]
 
 _F = np.float64
 
 
+def halton_offsets(P, Q):
+    """The first Q distinct non-zero offsets floor(P h) mod P, h = 1/2, 1/4, 3/4, 1/8, 3/8, ...
+    (fewer if the sequence runs out of new offsets: at most P - 1 exist)."""
+    out, level = [], 2
+    while len(out) < Q and level <= 2 * P:
+        for num in range(1, level, 2):
+            off = (P * num // level) % P
+            if off != 0 and off not in out:
+                out.append(off)
+                if len(out) == Q:
+                    break
+        level *= 2
+    return out
+
+
+def halton_receivers(P, Q):
+    """receivers[p] = the workers p broadcasts to under Halton sequence broadcast."""
+    offs = halton_offsets(P, Q)
+    return [[(p + o) % P for o in offs] for p in range(P)]
+
+
 class SspOracle:
-    def __init__(self, model, W0, P, B, staleness):
+    def __init__(self, model, W0, P, B, staleness, receivers=None, queue=None):
         assert model in _o.MODELS and staleness >= 0
         self.model, self.P, self.B, self.s = model, int(P), int(B), int(staleness)
+        if receivers is None:
+            receivers = [[p for p in range(self.P) if p != q] for q in range(self.P)]
+        self.receivers = [sorted(set(int(p) for p in r) - {q}) for q, r in enumerate(receivers)]
+        self.senders = [[q for q in range(self.P) if p in self.receivers[q]] for p in range(self.P)]
+        self.queue = queue
         self.W0 = np.asarray(W0, dtype=_F).copy()
         self.t = [0] * self.P                                   # iterations completed
         self.tau = [[0] * self.P for _ in range(self.P)]        # tau[p][q]
@@ -73,11 +111,15 @@ class SspOracle:
         return W
 
     # -- the schedule's rules -------------------------------------------------
+    def queue_full(self, p):
+        return self.queue is not None and any(self.t[p] - self.tau[r][p] >= self.queue for r in self.receivers[p])
+
     def may_step(self, p):
-        return all(self.t[p] - self.tau[p][q] <= self.s for q in range(self.P) if q != p)
+        return all(self.t[p] - self.tau[p][q] <= self.s for q in self.senders[p]) and not self.queue_full(p)
 
     def may_deliver(self, p, q, count=1):
-        return p != q and count >= 0 and self.tau[p][q] + count <= self.t[q] and self.tau[p][q] + count <= self.t[p]
+        return (p != q and p in self.receivers[q] and count >= 0 and self.tau[p][q] + count <= self.t[q]
+                and self.tau[p][q] + count <= self.t[p])
 
     # -- events ---------------------------------------------------------------
     def worker_step(self, p, batch_p, eta):

@@ -11,7 +11,7 @@ import pytest
 
 import oracle
 import workloads
-from oracle.ssp_oracle import SspOracle
+from oracle.ssp_oracle import SspOracle, halton_offsets, halton_receivers
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "ssp_hand_example.json")
 
@@ -167,3 +167,115 @@ def test_replicas_disagree_under_staleness_and_not_without():
     want = o.partial_update(0, 0) + o.partial_update(0, 1) - o.partial_update(1, 0)
     np.testing.assert_allclose(gap, want, rtol=1e-12, atol=1e-16)
     assert np.abs(gap).max() > 1e-6
+
+
+# -- partial broadcast (Section 4.3) ----------------------------------------------------------
+HSB = os.path.join(os.path.dirname(__file__), "golden", "hsb_hand_example.json")
+
+
+def test_halton_peers_are_the_papers_example():
+    g = json.load(open(HSB))
+    ex = g["paper_example"]
+    assert halton_offsets(ex["P"], ex["Q"]) == ex["offsets"]
+    rec = halton_receivers(ex["P"], ex["Q"])
+    for p in range(ex["P"]):
+        assert sorted(rec[p]) == sorted([(p + 3) % 6, (p + 1) % 6])
+    for label, peers in ex["one_based"].items():            # the paper's labels: machine 6 is index 0
+        assert sorted(rec[int(label) % 6]) == sorted(q % 6 for q in peers)
+    assert halton_offsets(16, 5) == g["printed_sequence_times_16"]
+
+
+@pytest.mark.parametrize("P,Q", [(6, 2), (12, 4), (16, 5), (7, 3), (5, 9)])
+def test_halton_topology_is_a_circulant_with_q_distinct_peers(P, Q):
+    rec = halton_receivers(P, Q)
+    want = min(Q, P - 1)
+    offs = halton_offsets(P, Q)
+    assert len(offs) == len(set(offs)) == want and all(0 < o < P for o in offs)
+    for p in range(P):
+        assert len(set(rec[p])) == want and p not in rec[p]
+        assert sum(p in rec[q] for q in range(P)) == want           # as many senders as receivers
+    if Q >= P - 1:
+        assert all(sorted(rec[p]) == [q for q in range(P) if q != p] for p in range(P))
+
+
+def hsb_hand_example(cls=SspOracle, receivers=None):
+    g = json.load(open(HSB))
+    rec = halton_receivers(g["P"], g["Q"]) if receivers is None else receivers
+    o = cls(g["model"], np.array([[g["W0"]]]), g["P"], g["B"], g["staleness"], receivers=rec)
+    shares = [lambda t, a=a: {"X": np.array([[a]]), "Y": np.array([[0.0]]), "y": np.array([1])}
+              for a in g["pair_difference"]]
+    rows = []
+    for ev in g["events"]:
+        flag = replay(o, [tuple(ev)], shares, g["eta"])[0]
+        rows.append((flag, [o.replica(p)[0, 0] for p in range(g["P"])]))
+    return g, rows
+
+
+def hsb_matches(cls=SspOracle, receivers=None):
+    g, rows = hsb_hand_example(cls, receivers)
+    return ([r[0] for r in rows] == g["accepted"]
+            and np.allclose([r[1] for r in rows], g["w_after"], rtol=0, atol=1e-12))
+
+
+def test_hand_worked_partial_broadcast_schedule():
+    assert hsb_matches()
+
+
+class _StalenessOverEveryWorker(SspOracle):
+    """Planted mistake: the pause rule also waits for workers that never send to p."""
+    def may_step(self, p):
+        return all(self.t[p] - self.tau[p][q] <= self.s for q in range(self.P) if q != p)
+
+
+class _DeliversAlongMissingEdges(SspOracle):
+    """Planted mistake: the topology is ignored when something is delivered."""
+    def may_deliver(self, p, q, count=1):
+        return p != q and count >= 0 and self.tau[p][q] + count <= self.t[q] and self.tau[p][q] + count <= self.t[p]
+
+
+def test_planted_mistakes_fail_the_partial_broadcast_example():
+    assert not hsb_matches(_StalenessOverEveryWorker)
+    assert not hsb_matches(_DeliversAlongMissingEdges)
+    assert not hsb_matches(receivers=[[2], [0], [1]])            # the ring the other way round
+    # the textbook (bit-reversed) base-2 Halton order would put 5/8 before 3/8
+    assert halton_offsets(16, 5)[4] == 6 != 10
+
+
+def test_full_halton_broadcast_is_the_plain_ssp_oracle():
+    wl = workloads.make("mlr_tiny", seed=4, J=4, D=9, P=4, B=2)
+    a = SspOracle(wl.model, wl.W0, wl.P, wl.B, 1)
+    b = SspOracle(wl.model, wl.W0, wl.P, wl.B, 1, receivers=halton_receivers(wl.P, wl.P - 1))
+    for ev in workloads.ssp_proposals(wl.P, 200, seed=4):
+        outs = []
+        for o in (a, b):
+            if ev[0] == "step":
+                outs.append(o.t[ev[1]] < 8 and o.worker_step(
+                    ev[1], workloads.worker_share(wl.model, wl.batch(o.t[ev[1]]), ev[1], wl.B), wl.eta) is not None)
+            else:
+                outs.append(o.deliver(ev[1], ev[2], ev[3]))
+        assert outs[0] == outs[1]
+    for p in range(wl.P):
+        np.testing.assert_array_equal(a.replica(p), b.replica(p))
+
+
+def test_send_queue_bounds_how_far_a_sender_runs_ahead_of_a_receiver():
+    """Ring 0 -> 1 -> 2 -> 0, staleness 1: worker 0 is paced by its sender 2 only, so worker 1 can
+    fall behind in applying worker 0's sets; the queue stops worker 0 when it holds `queue` of them."""
+    wl = workloads.make("mlr_tiny", seed=6, J=3, D=5, P=3, B=2)
+    o = SspOracle(wl.model, wl.W0, wl.P, wl.B, 1, receivers=halton_receivers(3, 1), queue=3)
+    share = lambda p: workloads.worker_share(wl.model, wl.batch(o.t[p]), p, wl.B)
+    steps0 = 0
+    for _ in range(10):
+        for p in (1, 2):                                     # 1 and 2 keep going as far as they may ...
+            if o.may_step(p):
+                o.worker_step(p, share(p), wl.eta)
+        while o.may_deliver(0, 2, 1):                        # ... and worker 0 receives everything from 2
+            o.deliver(0, 2, 1)
+        while o.may_deliver(2, 1, 1):
+            o.deliver(2, 1, 1)
+        if o.worker_step(0, share(0), wl.eta) is not None:   # but worker 1 never applies worker 0's sets
+            steps0 += 1
+    # the staleness chain alone (1 waits for 0's sets, 2 for 1's, 0 for 2's) would allow a fourth
+    assert steps0 == 3 and o.queue_full(0) and o.t[0] - o.tau[1][0] == 3
+    assert all(o.t[0] - o.tau[0][q] <= o.s for q in o.senders[0])
+    assert o.deliver(1, 0, 1) and not o.queue_full(0) and o.may_step(0)
