@@ -310,16 +310,29 @@ SFB_API sfb_status sfb_ssp_create(sfb_ssp **out, sfb_ctx *ctx, int32_t staleness
 SFB_API void sfb_ssp_destroy(sfb_ssp *ssp);
 /* Worker p's next iteration on its own B samples (as in sfb_compute_factors_worker), at its
  * own replica: factors into the ring, own update applied, t_p += 1.  If the staleness rule
- * forbids it, *blocked = 1 and nothing else happens (SFB_OK); else *blocked = 0.
- * loss: base of a DEVICE [N] fp32 array of which rows [p*B, (p+1)*B) are written, or NULL.
- * SFB_EUNSUPPORTED if the ring slot of this iteration still holds a set some replica has not
- * applied (cannot happen with ring_slots >= 2*staleness + 2). */
+ * forbids it, *blocked = 1 and nothing else happens (SFB_OK); if the ring slot of this
+ * iteration still holds a set that one of p's receivers has not applied (the send queue is
+ * full: cannot happen under full broadcast with ring_slots >= 2*staleness + 2), *blocked = 2
+ * and nothing else happens; else *blocked = 0.
+ * loss: base of a DEVICE [N] fp32 array of which rows [p*B, (p+1)*B) are written, or NULL. */
 SFB_API sfb_status sfb_ssp_worker_step(sfb_ssp *ssp, int32_t p, const sfb_batch *batch_p, const int32_t *y_p,
                                float eta, float *loss, int32_t *blocked);
 /* Replica p receives and applies the next `count` factor sets of worker q, oldest first.
  * SFB_EINVAL (nothing applied) if p == q, or q has not produced that many, or it would break
  * the no-fast-forward rule. */
 SFB_API sfb_status sfb_ssp_deliver(sfb_ssp *ssp, int32_t p, int32_t q, int32_t count);
+/*
+ * Partial broadcast (Section 4.3, Halton sequence broadcast): `sends` is a HOST P x P byte
+ * matrix, sends[q*P + p] != 0 meaning worker q's factors go to replica p (the diagonal is
+ * ignored).  The staleness rule then ranges over the workers that send to p, a delivery along
+ * a missing edge is SFB_EINVAL, and the replicas no longer agree when everything has arrived.
+ * Only before the first iteration (SFB_EINVAL afterwards).  Default: full broadcast.
+ */
+SFB_API sfb_status sfb_ssp_set_receivers(sfb_ssp *ssp, const uint8_t *sends);
+/* The topology of Section 4.3: worker p sends to (p + floor(P h)) mod P for the first Q terms h
+ * of 1/2, 1/4, 3/4, 1/8, 3/8, ... that give a new non-zero offset (at most P - 1 exist).
+ * sends: HOST [P][P] bytes, overwritten.  SFB_EINVAL for P < 1, Q < 0 or a null pointer. */
+SFB_API sfb_status sfb_halton_receivers(int32_t P, int32_t Q, uint8_t *sends);
 /* Clocks: t [P] and tau [P][P] (row p = replica p), HOST int32 arrays; either may be NULL. */
 SFB_API sfb_status sfb_ssp_state(const sfb_ssp *ssp, int32_t *t, int32_t *tau);
 

@@ -6,6 +6,6 @@ been built (python paper_1511_08486_amd/build.py, or __graft_entry__.build()).  
 is no CPU fallback.
 """
 from .binding import (  # noqa: F401
-    SFB_MLR, SFB_DML, SFB_L2SVM, SFB_F32, SFB_BF16, SfbError, SfbBatch, Sfb, SspSimulator, lib, library_path,
+    SFB_MLR, SFB_DML, SFB_L2SVM, SFB_F32, SFB_BF16, SfbError, SfbBatch, Sfb, SspSimulator, halton_receivers, lib, library_path,
     sfb_strerror,
 )

@@ -73,6 +73,8 @@ def _load():
         "sfb_ssp_destroy": (None, [vp]),
         "sfb_ssp_worker_step": (C.c_int, [vp, i32, pb, vp, f32, vp, C.POINTER(i32)]),
         "sfb_ssp_deliver": (C.c_int, [vp, i32, i32, i32]),
+        "sfb_ssp_set_receivers": (C.c_int, [vp, vp]),
+        "sfb_halton_receivers": (C.c_int, [i32, i32, vp]),
         "sfb_ssp_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32)]),
     }
     for name, (res, args) in sigs.items():
@@ -289,11 +291,22 @@ class Sfb:
         self._check(lib.sfb_reset_timing(self._ctx), "sfb_reset_timing")
 
 
+def halton_receivers(P, Q):
+    """receivers[p] = sorted workers that p broadcasts to under Halton sequence broadcast
+    (computed by the library: sfb_halton_receivers)."""
+    m = (C.c_uint8 * (P * P))()
+    status = lib.sfb_halton_receivers(int(P), int(Q), m)
+    if status != 0:
+        raise SfbError(status, "sfb_halton_receivers")
+    return [[r for r in range(P) if m[p * P + r]] for p in range(P)]
+
+
 class SspSimulator:
     """Stale-synchronous SFB on one device: owns P replicas of W and the ring of factor sets,
-    forwards every event to the sfb_ssp_* entry points (which keep the clocks and the rules)."""
+    forwards every event to the sfb_ssp_* entry points (which keep the clocks and the rules).
+    receivers[q] (optional) = the workers q broadcasts to; default: everybody."""
 
-    def __init__(self, ctx, W0, staleness, ring_slots=None):
+    def __init__(self, ctx, W0, staleness, ring_slots=None, receivers=None):
         self.ctx, self.s = ctx, int(staleness)
         self.slots = int(ring_slots) if ring_slots is not None else 2 * self.s + 2
         dev = ctx.device
@@ -307,13 +320,22 @@ class SspSimulator:
         ctx._check(lib.sfb_ssp_create(C.byref(self._ssp), ctx._ctx, self.s, ptrs, self.W[0].stride(0),
                                       self.U_ring.data_ptr(), self.U_ring.stride(1), self.V_ring.data_ptr(),
                                       self.V_ring.stride(1), self.slots), "sfb_ssp_create")
+        if receivers is not None:
+            P = ctx.P
+            m = (C.c_uint8 * (P * P))()
+            for q, rs in enumerate(receivers):
+                for r in rs:
+                    m[q * P + int(r)] = 1
+            ctx._check(lib.sfb_ssp_set_receivers(self._ssp, m), "sfb_ssp_set_receivers")
 
     def worker_step(self, p, batch_p, y_p, eta, loss=None):
-        """True if worker p ran its next iteration, False if the staleness rule made it pause."""
+        """True if worker p ran its next iteration, False if it had to pause (the staleness rule,
+        or its send queue -- the ring -- is full); self.last_blocked says which (1 or 2)."""
         b = batch_p.c_struct()
         blocked = C.c_int32(0)
         self.ctx._check(lib.sfb_ssp_worker_step(self._ssp, int(p), C.byref(b), y_p.data_ptr(), float(eta),
                                                 _ptr(loss), C.byref(blocked)), "sfb_ssp_worker_step")
+        self.last_blocked = blocked.value
         return blocked.value == 0
 
     def deliver(self, p, q, count=1):

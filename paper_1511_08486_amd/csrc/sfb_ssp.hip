@@ -20,6 +20,7 @@ struct sfb_ssp {
     std::vector<int32_t> t;              // [P]   iterations completed
     std::vector<int32_t> tau;            // [P][P] sets of q applied at replica p
     std::vector<float> eta;              // [slots][P] step size of the set held in that slot
+    std::vector<uint8_t> sends;          // [P][P] sends[q * P + p] != 0: worker q's factors go to replica p
 };
 
 namespace {
@@ -60,6 +61,7 @@ sfb_status sfb_ssp_create(sfb_ssp** out, sfb_ctx* ctx, int32_t staleness, float*
     s->t.assign(P, 0);
     s->tau.assign((size_t)P * P, 0);
     s->eta.assign((size_t)ring_slots * P, 0.f);
+    s->sends.assign((size_t)P * P, 1);   // full broadcast
     *out = s;
     return SFB_OK;
 }
@@ -72,15 +74,19 @@ sfb_status sfb_ssp_worker_step(sfb_ssp* s, int32_t p, const sfb_batch* batch_p, 
     if (p < 0 || p >= s->P) return SFB_ESHAPE;
     const int32_t P = s->P, c = s->t[p];
     for (int32_t q = 0; q < P; ++q) {
-        if (q != p && c - s->tau[(size_t)p * P + q] > s->staleness) {
-            *blocked = 1;            // some q is more than `staleness` iterations behind from p's point of view
+        if (q != p && s->sends[(size_t)q * P + p] && c - s->tau[(size_t)p * P + q] > s->staleness) {
+            *blocked = 1;            // some sender q is more than `staleness` iterations behind from p's point of view
+            return SFB_OK;
+        }
+    }
+    // the slot of iteration c is free once every receiver has applied iteration c - slots of worker p
+    for (int32_t r = 0; r < P; ++r) {
+        if (r != p && s->sends[(size_t)p * P + r] && c - s->tau[(size_t)r * P + p] >= s->slots) {
+            *blocked = 2;            // send queue full
             return SFB_OK;
         }
     }
     *blocked = 0;
-    // the slot of iteration c is free once every replica has applied iteration c - slots of worker p
-    for (int32_t r = 0; r < P; ++r)
-        if (c - s->tau[(size_t)r * P + p] >= s->slots && r != p) return SFB_EUNSUPPORTED;
     float* U = u_slot(s, c);
     void* V = v_slot(s, c);
     sfb_status st = sfb_compute_factors_worker(s->ctx, s->W[p], s->ldw, batch_p, y_p, p, U, s->ldu, V, s->ldv, loss);
@@ -99,6 +105,7 @@ sfb_status sfb_ssp_deliver(sfb_ssp* s, int32_t p, int32_t q, int32_t count) {
     if (p < 0 || p >= s->P || q < 0 || q >= s->P) return SFB_ESHAPE;
     if (p == q || count < 0) return SFB_EINVAL;
     const int32_t P = s->P;
+    if (!s->sends[(size_t)q * P + p]) return SFB_EINVAL;   // q does not broadcast to p
     const int32_t have = s->tau[(size_t)p * P + q];
     if (have + count > s->t[q]) return SFB_EINVAL;     // q has not produced that many
     if (have + count > s->t[p]) return SFB_EINVAL;     // no fast-forward
@@ -109,6 +116,34 @@ sfb_status sfb_ssp_deliver(sfb_ssp* s, int32_t p, int32_t q, int32_t count) {
         if (st != SFB_OK) return st;
         s->tau[(size_t)p * P + q] = it + 1;
     }
+    return SFB_OK;
+}
+
+sfb_status sfb_ssp_set_receivers(sfb_ssp* s, const uint8_t* sends) {
+    if (!s || !sends) return SFB_EINVAL;
+    // only before anything has been produced: the clocks assume one topology throughout
+    for (int32_t p = 0; p < s->P; ++p)
+        if (s->t[p] != 0) return SFB_EINVAL;
+    s->sends.assign(sends, sends + (size_t)s->P * s->P);
+    return SFB_OK;
+}
+
+sfb_status sfb_halton_receivers(int32_t P, int32_t Q, uint8_t* sends) {
+    if (P < 1 || Q < 0 || !sends) return SFB_EINVAL;
+    for (size_t i = 0; i < (size_t)P * P; ++i) sends[i] = 0;
+    // offsets floor(P * num / level) for level = 2, 4, 8, ... and odd num ascending (the order
+    // Section 4.3 prints: P/2, P/4, 3P/4, P/8, 3P/8, ...); zero and repeated offsets are skipped
+    std::vector<int32_t> offs;
+    for (int64_t level = 2; (int32_t)offs.size() < Q && level <= 2 * (int64_t)P; level *= 2) {
+        for (int64_t num = 1; num < level && (int32_t)offs.size() < Q; num += 2) {
+            const int32_t off = (int32_t)(((int64_t)P * num / level) % P);
+            bool seen = off == 0;
+            for (int32_t o : offs) seen = seen || o == off;
+            if (!seen) offs.push_back(off);
+        }
+    }
+    for (int32_t p = 0; p < P; ++p)
+        for (int32_t o : offs) sends[(size_t)p * P + (p + o) % P] = 1;
     return SFB_OK;
 }
 

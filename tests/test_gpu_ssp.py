@@ -142,3 +142,66 @@ def test_ring_too_small_is_refused(sfb):
     with pytest.raises(sfb.SfbError):
         sfb.SspSimulator(ctx, torch.from_numpy(wl.W0), 2, ring_slots=5)
     ctx.close()
+
+
+@pytest.mark.parametrize("name,override,s,Q,seed", [
+    ("mlr_tiny", dict(J=10, D=100, P=6, B=4), 1, 2, 0),
+    ("mlr_medium", dict(J=136, D=256, P=5, B=32), 2, 2, 1),
+    ("dml", dict(J=24, D=128, P=4, B=8), 0, 1, 2),
+])
+def test_halton_partial_broadcast_matches_the_oracle(sfb, name, override, s, Q, seed):
+    """Section 4.3: every worker sends to Q peers only.  Same proposals on both sides; accept flags and
+    clocks agree exactly, replicas within tolerance -- and they do NOT agree with each other at the end."""
+    wl = workloads.make(name, seed=seed, **override)
+    dev = "cuda:0"
+    rec = sfb.halton_receivers(wl.P, Q)
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
+    slots = 2 * s + 2
+    sim = sfb.SspSimulator(ctx, torch.from_numpy(wl.W0), s, ring_slots=slots, receivers=rec)
+    o = SspOracle(wl.model, wl.W0, wl.P, wl.B, s, receivers=rec, queue=slots)
+    accepted = refused_edges = queue_blocks = 0
+    for k, ev in enumerate(workloads.ssp_proposals(wl.P, 260, seed=seed)):
+        if ev[0] == "step":
+            p = ev[1]
+            if o.t[p] >= 6:
+                continue
+            share, (db, dy) = device_share(sfb, wl, wl.batch(o.t[p]), p, dev)
+            was_full = o.queue_full(p)
+            got = sim.worker_step(p, db, dy, wl.eta)
+            want = o.worker_step(p, share, wl.eta) is not None
+            if not got:
+                assert sim.last_blocked == (1 if not all(o.t[p] - o.tau[p][q] <= s for q in o.senders[p]) else 2)
+                queue_blocks += was_full
+        else:
+            got = sim.deliver(ev[1], ev[2], ev[3])
+            want = o.deliver(ev[1], ev[2], ev[3])
+            refused_edges += ev[1] != ev[2] and ev[1] not in rec[ev[2]]
+        assert got == want, f"event {k} {ev}: accepted on the device = {got}, in the oracle = {want}"
+        accepted += got
+    ctx.sync()
+    t, tau = sim.state()
+    assert t == o.t and tau == o.tau
+    assert accepted > 40 and refused_edges > 5
+    for p in range(wl.P):
+        assert_close(sim.W[p].cpu().numpy(), o.replica(p), TOL32, f"replica {p}")
+        for q in range(wl.P):
+            if q != p and p not in rec[q]:
+                assert tau[p][q] == 0                      # nothing ever arrives along a missing edge
+    spread = max(float((sim.W[p] - sim.W[0]).abs().max()) for p in range(1, wl.P))
+    assert spread > 1e-5, "partial broadcast should leave the replicas different"
+    sim.close()
+    ctx.close()
+
+
+def test_receivers_can_only_be_set_before_the_first_iteration(sfb):
+    import ctypes as C
+    wl = workloads.make("mlr_tiny")
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device="cuda:0")
+    sim = sfb.SspSimulator(ctx, torch.from_numpy(wl.W0), 1)
+    share, (db, dy) = device_share(sfb, wl, wl.batch(0), 0, "cuda:0")
+    assert sim.worker_step(0, db, dy, wl.eta)
+    m = (C.c_uint8 * (wl.P * wl.P))(*([1] * (wl.P * wl.P)))
+    assert sfb.lib.sfb_ssp_set_receivers(sim._ssp, m) == -1
+    ctx.sync()
+    sim.close()
+    ctx.close()

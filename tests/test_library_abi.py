@@ -148,6 +148,17 @@ def test_ssp_and_per_sender_calls_validate_before_launching(lib):
     assert lib.sfb_ssp_worker_step(ssp, 0, None, None, 0.1, None, None) == -1
     assert lib.sfb_ssp_worker_step(ssp, 0, None, fake, 0.1, None, C.byref(blocked)) == -1     # no batch: refused by the factor call
     assert list(t) == [0, 0, 0]
+    # partial broadcast: 0 -> 1 -> 2 -> 0
+    assert lib.sfb_ssp_set_receivers(ssp, None) == -1 and lib.sfb_ssp_set_receivers(None, reps) == -1
+    ring = (C.c_uint8 * 9)(0, 1, 0, 0, 0, 1, 1, 0, 0)
+    assert lib.sfb_ssp_set_receivers(ssp, ring) == 0
+    assert lib.sfb_ssp_deliver(ssp, 0, 1, 0) == -1          # worker 1 does not send to worker 0 (even for count 0)
+    assert lib.sfb_ssp_deliver(ssp, 1, 0, 0) == 0
+    m = (C.c_uint8 * 36)()
+    assert lib.sfb_halton_receivers(6, 2, m) == 0
+    assert [[r for r in range(6) if m[p * 6 + r]] for p in range(6)] == [[1, 3], [2, 4], [3, 5], [0, 4], [1, 5], [0, 2]]
+    assert lib.sfb_halton_receivers(0, 2, m) == -1 and lib.sfb_halton_receivers(6, -1, m) == -1
+    assert lib.sfb_halton_receivers(6, 2, None) == -1
     lib.sfb_ssp_destroy(ssp)
     lib.sfb_destroy(ctx)
 
