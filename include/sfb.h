@@ -253,7 +253,7 @@ SFB_API int sfb_last_hip_error(const sfb_ctx *ctx);
  * enable it while the stream is being captured into a graph); sfb_kernel_time_ms synchronises
  * and returns the accumulated milliseconds and launch count of kernel family `which`
  * (0 = scores, 1 = factor u, 2 = reconstruct-apply: the contraction, without the bf16 path's
- * operand-packing kernel, 3 = CSR densify / stream copy) since the last reset.
+ * operand-packing kernel, 3 = CSR densify / stream copy, 4 = proximal step) since the last reset.
  */
 SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32_t *fwd_grid,
                          int32_t *recon_grid);
@@ -269,8 +269,8 @@ SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32
  * exactly into three bf16 terms and every product taken as its six leading term products (error
  * at the level of one fp32 rounding; full batch and 16-byte aligned rows only, else ignored);
  * bit 3 = the same for the fp32 reconstruction (J, D multiples of 4, N a multiple of 32, no dead
- * workers, else ignored); < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.  The workspace requirement may grow:
- * query sfb_workspace_bytes again.  SFB_EINVAL for a value outside the table. */
+ * workers, else ignored); < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.
+ * The workspace requirement may grow: query sfb_workspace_bytes again.  SFB_EINVAL for a value outside the table. */
 SFB_API sfb_status sfb_set_plan(sfb_ctx *ctx, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k,
                                 int32_t recon_variant, int32_t fwd_dma);
 /* Measurement aid, not part of the method: dst[0..bytes) = src[0..bytes) with a plain streaming
