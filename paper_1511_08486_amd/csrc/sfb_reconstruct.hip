@@ -302,8 +302,8 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
 // ---------------------------------------------------------------------------------------
 
 // BK factor pairs per stage, NST stages in the ring (NST - 1 of them in flight ahead).
-template <int MT, int NWR, int BK, int NST>
-__global__ __launch_bounds__(NWR * 64, 1) void reconstruct_apply_dma_kernel(
+template <int MT, int NWR, int BK, int NST, int WPS>
+__global__ __launch_bounds__(NWR * 64, WPS) void reconstruct_apply_dma_kernel(
     float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const float* __restrict__ V,
     int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total, int prox_kind, float prox_a) {
     constexpr int BN = kReconBN, G = kReconGroup;
@@ -504,7 +504,7 @@ __global__ __launch_bounds__(NWR * 64, 1) void reconstruct_apply_dma_kernel(
         }
 }
 
-template <int MT, int NWR, int BK, int NST>
+template <int MT, int NWR, int BK, int NST, int WPS = 1>
 static hipError_t launch_recon_dma(const ReconArgs& a, hipStream_t s) {
     constexpr int BM = 32 * MT * NWR;
     const int n_jb = (a.J + BM - 1) / BM, n_db = a.D / kReconBN;
@@ -512,12 +512,12 @@ static hipError_t launch_recon_dma(const ReconArgs& a, hipStream_t s) {
     constexpr size_t lds_bytes = (size_t)NST * BK * (BM + kReconBN) * sizeof(float);
     static bool raised = false;
     if (lds_bytes > 64 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_dma_kernel<MT, NWR, BK, NST>,
+        hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_dma_kernel<MT, NWR, BK, NST, WPS>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    SFB_LAUNCH((reconstruct_apply_dma_kernel<MT, NWR, BK, NST>), dim3(total), dim3(NWR * 64), lds_bytes, s, a.w,
+    SFB_LAUNCH((reconstruct_apply_dma_kernel<MT, NWR, BK, NST, WPS>), dim3(total), dim3(NWR * 64), lds_bytes, s, a.w,
                        a.ldw, a.u, a.ldu, (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total, a.prox_kind,
                        a.prox_a);
     return hipGetLastError();
@@ -542,6 +542,7 @@ static const ReconVariant kReconVariants[] = {
     {1, 4, 1, true},   // 7: 128 x 128, 4 wavefronts, LDS-DMA staging (falls back to 0)
     {1, 2, 1, true},   // 8: 64 x 128, 2 wavefronts, LDS-DMA staging (falls back to 1)
     {1, 2, 1, true},   // 9: 64 x 64, 4 wavefronts of one 32 x 32 block each, LDS-DMA staging (falls back to 8)
+    {1, 4, 1, true},   // 10: as 7 with 16-pair stages and a register budget for two workgroups per compute unit
 };
 constexpr int kSmallVariant = 9;
 constexpr int kNumReconVariants = sizeof(kReconVariants) / sizeof(kReconVariants[0]);
@@ -566,6 +567,15 @@ ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
         // tile is used for its four wavefronts (more lanes to fetch with; the surplus
         // wavefronts multiply clamped rows that are never stored)
         variant = J > 64 ? 8 : 7;
+    }
+    // Several tiles per compute unit: 16-pair stages (48 KB of LDS) and a register budget that
+    // lets two workgroups share a compute unit, so that one multiplies while the other fetches
+    // its first stage or writes its tile back (measured, dense factors: J = 2000, D = 8192,
+    // N = 1024: 316 -> 277 us; 4096 x 4096, N = 512: 154 -> 142 us).  With one tile per compute
+    // unit there is nothing to overlap with and the shorter stages only cost (40.2 -> 42.6 us).
+    if (variant == 7) {
+        const int64_t tiles = ((J + 127) / 128) * ((D + kReconBN - 1) / kReconBN);
+        if (tiles >= 512) variant = 10;
     }
     // single-block wavefronts where the lumps of four blocks would leave the busiest SIMD with
     // clearly more than its share (e.g. J = 600: 3 blocks instead of 4)
@@ -638,6 +648,10 @@ hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_
         q.variant = 8;
     }
     if (kReconVariants[q.variant].dma) {
+        if (q.variant == 10) {
+            if (dma_ok(a, 16)) return launch_recon_dma<1, 4, 16, 3, 2>(a, s);
+            q.variant = 7;
+        }
         if (dma_ok(a, kReconBK)) {
             switch (q.variant) {
                 case 7: return launch_recon_dma<1, 4, kReconBK, 3>(a, s);

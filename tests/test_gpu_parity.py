@@ -61,8 +61,8 @@ def test_every_tile_variant(sfb, plan):
     run_chain(wl, 2, TOL32, plan=plan)
 
 
-@pytest.mark.parametrize("variant", [7, 8])
-@pytest.mark.parametrize("J,D,P,B", [(520, 1024, 4, 48), (1000, 4096, 8, 64), (36, 256, 1, 32)])
+@pytest.mark.parametrize("variant", [7, 8, 10])
+@pytest.mark.parametrize("J,D,P,B", [(520, 1024, 4, 48), (1000, 4096, 8, 64), (36, 256, 1, 32), (2000, 8192, 1, 16)])
 def test_lds_dma_reconstruct_variants(sfb, variant, J, D, P, B):
     """Shapes the LDS-DMA staging accepts (D % 128 == 0, J % 4 == 0, N % 32 == 0)."""
     wl = workloads.make("mlr_medium", seed=variant, J=J, D=D, P=P, B=B, steps=3, pool=2)
