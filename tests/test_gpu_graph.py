@@ -47,3 +47,57 @@ def test_step_recorded_in_a_graph_replays_like_eager_steps(name, over):
         scratch.add_(1.0)                          # unrelated eager work between replays
         torch.cuda.synchronize()
     ctx.close()
+
+
+@pytest.mark.parametrize("what", ["step_prox_l1", "step_prox_column_ball", "sdca_step"])
+def test_proximal_and_sdca_iterations_replay_like_eager_ones(what):
+    """The proximal iteration (fused entrywise operator; column projection with its three kernels
+    and workspace) and the SDCA iteration (dual vectors updated in place) are plain launches too."""
+    import paper_1511_08486_amd as sfb
+    dev = "cuda:0"
+    side = torch.cuda.Stream(device=dev)
+    with torch.cuda.stream(side):
+        if what == "sdca_step":
+            wl = workloads.make_sdca("sdca_tiny", seed=2, J=40, D=256, n_data=96, P=2, B=16)
+            ctx = sfb.Sfb("mlr", wl.J, wl.D, wl.P, wl.B, device=dev)
+            A, yd = torch.from_numpy(wl.A).to(dev), torch.from_numpy(wl.y).to(dev)
+            idx = torch.from_numpy(wl.pick(0)).to(dev)
+            batch, yb = sfb.SfbBatch(a=A[idx.long()].contiguous()), yd[idx.long()].contiguous()
+            W = torch.zeros((wl.J, wl.D), device=dev)
+            dual = torch.zeros((wl.n_data, wl.J), device=dev)
+            state = [W, dual]
+            U = torch.empty((wl.N, wl.J), device=dev)
+            V = torch.empty((wl.N, wl.D), device=dev)
+            run = lambda: ctx.sdca_step(W, batch, yb, dual, idx, wl.lam, 0.3, U, V)
+        else:
+            wl = workloads.make("mlr_medium", seed=3, pool=1, J=200, D=512, P=4, B=32)
+            ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+            batch, yb = to_device(wl, wl.batch(0), dev)
+            W = torch.from_numpy(wl.W0).to(dev)
+            state = [W]
+            U, V, _ = alloc_factors(wl, dev)
+            kind, param = ("l1", 1e-3) if what == "step_prox_l1" else ("column_ball", 1.3)
+            run = lambda: ctx.step_prox(W, batch, yb, U, V, wl.eta, kind, param)
+        start = [s.clone() for s in state]
+        ref = []
+        for _ in range(4):
+            run()
+            ctx.sync()
+            ref.append([s.clone() for s in state] + [U.clone()])
+        for s, s0 in zip(state, start):
+            s.copy_(s0)
+        side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run()
+    torch.cuda.synchronize()
+    assert all(torch.equal(s, s0) for s, s0 in zip(state, start))      # the capture ran nothing
+    scratch = torch.zeros(1 << 16, device=dev)
+    for t in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        for s, want in zip(state + [U], ref[t]):
+            assert torch.equal(s, want), f"{what}: replay {t} differs from the eager chain"
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
+    ctx.close()
