@@ -220,3 +220,24 @@ def test_prox_validates_before_launching(lib):
     assert lib.sfb_step_prox(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None, 0.1, None, 3, 0.0) == -1
     assert lib.sfb_step_prox(ctx, fake, 16, C.byref(b), fake, fake, 8, fake, 16, None, 0.1, None, 1, 0.1) == -5
     lib.sfb_destroy(ctx)
+
+
+def test_launch_plans_of_the_benchmark_shapes(lib):
+    """The planner is host code: tile counts for the five benchmark shapes (no GPU needed).
+    mlr_medium: 128x128 tiles, one per compute unit; dml: 600 rows take the 64x64 single-block tiles;
+    l2svm: 128x128 tiles, four per compute unit; mlr_large: 256x128 bf16 tiles."""
+    import paper_1511_08486_amd as sfb
+    want = {("mlr", 10, 100, 4, 16, "f32"): 1, ("mlr", 1000, 4096, 8, 64, "f32"): 256,
+            ("dml", 600, 4096, 8, 128, "f32"): 640, ("l2svm", 2000, 8192, 16, 64, "f32"): 1024}
+    for (model, J, D, P, B, dt), grid in want.items():
+        ctx = C.c_void_p()
+        assert lib.sfb_create(C.byref(ctx), sfb.binding._MODELS[model], J, D, P, B, sfb.binding._DTYPES[dt], None) == 0
+        k, g, r = C.c_int32(), C.c_int32(), C.c_int32()
+        assert lib.sfb_plan_info(ctx, C.byref(k), C.byref(g), C.byref(r)) == 0
+        assert r.value == grid, (model, J, D, r.value)
+        assert k.value >= 1 and g.value >= 1
+        # every variant of the table can be selected; one past the end cannot
+        for v in range(11):
+            assert lib.sfb_set_plan(ctx, 0, 0, 0, v, -1) == 0
+        assert lib.sfb_set_plan(ctx, 0, 0, 0, 11, -1) == -1
+        lib.sfb_destroy(ctx)
