@@ -86,6 +86,40 @@ __device__ __forceinline__ f32x4 load4_clamped(const bf16_t* __restrict__ base, 
     return r;
 }
 
+// The same four clamped scalar loads WITHOUT the zeroing select: nothing is computed from the
+// loaded words, so a prefetch can keep them in registers without the wait for them moving up
+// to the loads.  The consumer masks the elements outside the matrix (in_matrix4) when it uses
+// them.  bf16 comes back as its bit pattern, zero-extended by the load itself.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f32x4 load4_clamped_raw(const float* __restrict__ base, int64_t row, int64_t ld,
+                                                   int64_t nrows, int64_t col, int64_t ncols) {
+    const float* p = base + (row < nrows ? row : nrows - 1) * ld;
+    f32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = p[col + e < ncols ? col + e : ncols - 1];
+    return r;
+}
+__device__ __forceinline__ u32x4 load4_clamped_raw(const bf16_t* __restrict__ base, int64_t row, int64_t ld,
+                                                   int64_t nrows, int64_t col, int64_t ncols) {
+    const bf16_t* p = base + (row < nrows ? row : nrows - 1) * ld;
+    u32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = p[col + e < ncols ? col + e : ncols - 1];
+    return r;
+}
+__device__ __forceinline__ f32x4 widen4(u32x4 bits) {
+    f32x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = __uint_as_float(bits[e] << 16);
+    return r;
+}
+// v with the elements at columns >= ncols (or all of it, if !row_ok) replaced by 0
+__device__ __forceinline__ f32x4 in_matrix4(f32x4 v, bool row_ok, int64_t col, int64_t ncols) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (row_ok && col + e < ncols) ? v[e] : 0.f;
+    return v;
+}
+
 // Unguarded, aligned 4-element loads for the fast paths (the caller clamps the address
 // into the matrix and discards what it must not use: no branches around memory ops).
 __device__ __forceinline__ f32x4 ldg4(const float* __restrict__ p) { return *reinterpret_cast<const f32x4*>(p); }

@@ -15,6 +15,8 @@
 // holds C[8*(i/4) + 4*(l/32) + i%4][l%32] in accumulator element i.  The contraction
 // index is a dummy, so each lane reads four consecutive d with one 128-bit LDS read
 // and feeds them to four successive MFMAs (both operands use the same permutation).
+#include <type_traits>
+
 #include "sfb_device.h"
 #include "sfb_kernels.h"
 
@@ -65,8 +67,12 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
     const int n_chunks = (k_end - k_begin + BK - 1) / BK;
     const bool write_v = V != nullptr;   // shared by the class blocks: block jb takes the chunks c with c % n_jb == jb
 
+    // FAST: one wide load per item; otherwise four clamped scalar loads per item, kept as loaded
+    // (what lies outside the matrix or the slice is zeroed when the stage is written to LDS).
     using RawA = typename RawOf<TIn>::type;
-    struct Stage { RawA a[A_LD]; RawA a2[DIFF ? A_LD : 1]; f32x4 b[B_LD]; };
+    using RawSlow = typename std::conditional<std::is_same<TIn, float>::value, f32x4, u32x4>::type;
+    using RawS = typename std::conditional<FAST, RawA, RawSlow>::type;
+    struct Stage { RawS a[A_LD]; RawS a2[DIFF ? A_LD : 1]; f32x4 b[B_LD]; };
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
     // Raw words only: nothing may depend on a load before the stage that consumes it.
@@ -75,24 +81,24 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
         for (int i = 0; i < A_LD; ++i) {
             const int idx = tid + i * kFwdThreads;
             const int row = n0 + idx / (BK / 4), col = k0 + (idx % (BK / 4)) * 4;
-            if (FAST) {
+            if constexpr (FAST) {
                 const int64_t off = (int64_t)min(row, n_rows - 1) * lda + min(col, D - 4);
                 r.a[i] = ldraw4(A + off);
                 if (DIFF) r.a2[i] = ldraw4(A2 + off);
             } else {
-                // columns at or beyond k_end belong to the next slice: read them as 0
-                r.a[i] = to_raw<TIn>(load4_clamped(A, row, lda, n_rows, col, k_end));
-                if (DIFF) r.a2[i] = to_raw<TIn>(load4_clamped(A2, row, lda, n_rows, col, k_end));
+                // columns at or beyond k_end belong to the next slice: the stage zeroes them
+                r.a[i] = load4_clamped_raw(A, row, lda, n_rows, col, k_end);
+                if (DIFF) r.a2[i] = load4_clamped_raw(A2, row, lda, n_rows, col, k_end);
             }
         }
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
             const int idx = tid + i * kFwdThreads;
             const int row = j0 + idx / (BK / 4), col = k0 + (idx % (BK / 4)) * 4;
-            if (FAST) {
+            if constexpr (FAST) {
                 r.b[i] = ldg4(W + (int64_t)min(row, J - 1) * ldw + min(col, D - 4));
             } else {
-                r.b[i] = load4_clamped(W, row, ldw, J, col, k_end);
+                r.b[i] = load4_clamped_raw(W, row, ldw, J, col, k_end);
             }
         }
     };
@@ -107,10 +113,11 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
             f32x4 v = widen4(r.a[i]);
             if (DIFF) v -= widen4(r.a2[i]);
             const bool in = row < n_rows && col < k_end;   // FAST: k_end is a multiple of 4
-            if (FAST) v = in ? v : zero4;
+            if constexpr (FAST) v = in ? v : zero4;
+            else v = in_matrix4(v, row < n_rows, col, k_end);
             *reinterpret_cast<f32x4*>(&As[buf * BM * LS + rr * LS + cc]) = v;
             if (my_v && in) {
-                if (FAST) *reinterpret_cast<RawA*>(V + (int64_t)row * ldv + col) = to_raw<TIn>(v);
+                if constexpr (FAST) *reinterpret_cast<RawA*>(V + (int64_t)row * ldv + col) = to_raw<TIn>(v);
                 else store4(V + (int64_t)row * ldv, col, k_end, vec_v, v);
             }
         }
@@ -119,7 +126,8 @@ __global__ __launch_bounds__(kFwdThreads) void fwd_scores_kernel(
             const int idx = tid + i * kFwdThreads;
             const int rr = idx / (BK / 4), cc = (idx % (BK / 4)) * 4;
             f32x4 v = r.b[i];
-            if (FAST) v = (j0 + rr < J && k0 + cc < k_end) ? v : zero4;
+            if constexpr (FAST) v = (j0 + rr < J && k0 + cc < k_end) ? v : zero4;
+            else v = in_matrix4(v, j0 + rr < J, k0 + cc, k_end);
             *reinterpret_cast<f32x4*>(&Bs[buf * BN * LS + rr * LS + cc]) = v;
         }
     };

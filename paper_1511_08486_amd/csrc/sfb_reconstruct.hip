@@ -79,7 +79,11 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
 
     // Raw loaded words only: no arithmetic may depend on a load before the stage that
     // consumes it, or the wait for the load would move up to the load itself.
-    using RawV = typename RawOf<TV>::type;
+    // FAST: one wide load per item; otherwise four clamped scalar loads per item, kept as loaded
+    // (the elements outside the matrix are zeroed when the stage is written to LDS).
+    using RawFast = typename RawOf<TV>::type;
+    using RawSlow = typename std::conditional<std::is_same<TV, float>::value, f32x4, u32x4>::type;
+    using RawV = typename std::conditional<FAST, RawFast, RawSlow>::type;
     struct Stage { f32x4 u[U_LD]; RawV v[V_LD]; };
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
@@ -93,20 +97,20 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
         for (int i = 0; i < U_LD; ++i) {
             const int idx = tid + i * THREADS;
             const int k = k0 + idx / (BM / 4), c = j0 + (idx % (BM / 4)) * 4;
-            if (FAST) {
+            if constexpr (FAST) {
                 r.u[i] = ldg4(U + (int64_t)min(k, N - 1) * ldu + min(c, J - 4));
             } else {
-                r.u[i] = load4_clamped(U, k, ldu, N, c, J);
+                r.u[i] = load4_clamped_raw(U, k, ldu, N, c, J);
             }
         }
 #pragma unroll
         for (int i = 0; i < V_LD; ++i) {
             const int idx = tid + i * THREADS;
             const int k = k0 + idx / (BN / 4), c = d0 + (idx % (BN / 4)) * 4;
-            if (FAST) {
+            if constexpr (FAST) {
                 r.v[i] = ldraw4(V + (int64_t)min(k, N - 1) * ldv + c);
             } else {
-                r.v[i] = to_raw<TV>(load4_clamped(V, k, ldv, N, c, D));
+                r.v[i] = load4_clamped_raw(V, k, ldv, N, c, D);
             }
         }
     };
@@ -116,14 +120,18 @@ __global__ __launch_bounds__(NWR * KS * 64) void reconstruct_apply_kernel(
         for (int i = 0; i < U_LD; ++i) {
             const int idx = tid + i * THREADS;
             const int k = k0 + idx / (BM / 4), c = j0 + (idx % (BM / 4)) * 4;
-            const f32x4 v = (row_live(k) && c < J) ? r.u[i] * alpha : zero4;
+            f32x4 v;
+            if constexpr (FAST) v = (row_live(k) && c < J) ? r.u[i] * alpha : zero4;
+            else v = in_matrix4(r.u[i] * alpha, row_live(k), c, J);
             *reinterpret_cast<f32x4*>(&Us[buf * BK * BM + (idx / (BM / 4)) * BM + (idx % (BM / 4)) * 4]) = v;
         }
 #pragma unroll
         for (int i = 0; i < V_LD; ++i) {
             const int idx = tid + i * THREADS;
-            const int k = k0 + idx / (BN / 4);
-            const f32x4 v = row_live(k) ? widen4(r.v[i]) : zero4;
+            const int k = k0 + idx / (BN / 4), c = d0 + (idx % (BN / 4)) * 4;
+            f32x4 v;
+            if constexpr (FAST) v = row_live(k) ? widen4(r.v[i]) : zero4;
+            else v = in_matrix4(widen4(r.v[i]), row_live(k), c, D);
             *reinterpret_cast<f32x4*>(&Vs[buf * BK * BN + (idx / (BN / 4)) * BN + (idx % (BN / 4)) * 4]) = v;
         }
     };
