@@ -408,3 +408,30 @@ def test_w_with_more_than_2_to_31_entries(sfb, dtype, P, B):
     got_p = W[torch.from_numpy(rows).to(dev)][:, torch.from_numpy(cols).to(dev)].cpu().numpy()
     assert_close(got_p, oracle.prox("l2sq", want_w, 0.5, 1.0), tol, "sampled W after the proximal step")
     ctx.close()
+
+
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        model = ("mlr", "dml", "l2svm")[i % 3]
+        # a mix of ragged sizes and sizes on the kernels' alignment boundaries (4, 32, 64, 128)
+        J = int(rng.choice([rng.integers(1, 300), 4 * rng.integers(1, 80), 64 * rng.integers(1, 6)]))
+        D = int(rng.choice([rng.integers(1, 700), 64 * rng.integers(1, 12), 128 * rng.integers(1, 6)]))
+        P = int(rng.integers(1, 6))
+        B = int(rng.choice([rng.integers(1, 40), 16, 32]))
+        pad = int(rng.choice([0, 0, 1, 4]))
+        out.append((model, J, D, P, B, pad, 100 + i))
+    return out
+
+
+@pytest.mark.parametrize("model,J,D,P,B,pad,seed", _random_shapes(36, 2024))
+def test_random_shapes_through_the_default_plan(sfb, model, J, D, P, B, pad, seed):
+    """Whatever kernel the planner picks for a shape (LDS-DMA or register staging, 128-, 64-row or
+    single-block tiles, CSR or dense scores), two steps match the oracle."""
+    name = {"mlr": "mlr_tiny", "dml": "dml", "l2svm": "l2svm"}[model]
+    over = dict(J=J, D=D, P=P, B=B, steps=2, pool=2)
+    if model == "l2svm":
+        over["density"] = max(0.05, 1.5 / D)
+    wl = workloads.make(name, seed=seed, **over)
+    run_chain(wl, 2, TOL32, pad=pad, dml_guard=1e-6)
