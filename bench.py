@@ -49,6 +49,82 @@ def cpu_baseline(wl, budget_s):
             "steps_per_s": n / el}
 
 
+def bench_sdca(args):
+    """--config sdca_*: SFB driven by SDCA (Section 2.1) on a fixed synthetic data set.  A "step" is
+    one iteration over P*B distinct picked samples: scores, dual update + factors, reconstruction.
+    Same JSON keys as the main bench; informational (the headline configs are the SGD ones)."""
+    import numpy as np
+    import torch
+
+    import __graft_entry__
+    __graft_entry__.ensure_built()
+    import paper_1511_08486_amd as sfb
+    import workloads
+
+    dev = "cuda:0"
+    wl = workloads.make_sdca(args.config)
+    ctx = sfb.Sfb("mlr", wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
+    A = torch.from_numpy(wl.A).to(dev)
+    yd = torch.from_numpy(wl.y).to(dev)
+    pool = []
+    for t in range(min(len(wl.picks), 4)):                   # gathered batches resident in HBM
+        idx = torch.from_numpy(wl.pick(t)).to(dev)
+        pool.append((sfb.SfbBatch(a=A[idx.long()].contiguous()), yd[idx.long()].contiguous(), idx))
+    W = torch.zeros((wl.J, wl.D), dtype=torch.float32, device=dev)
+    dual = torch.zeros((wl.n_data, wl.J), dtype=torch.float32, device=dev)
+    U = torch.empty((wl.N, wl.J), dtype=torch.float32, device=dev)
+    V = torch.empty((wl.N, wl.D), dtype=torch.float32, device=dev)
+    s = 0.05
+
+    def run(k):
+        for t in range(k):
+            b, y, idx = pool[t % len(pool)]
+            ctx.sdca_step(W, b, y, dual, idx, wl.lam, s, U, V)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert bool(torch.isfinite(W).all())
+    ctx.enable_timing(True)
+    ctx.reset_timing()
+    run(min(args.steps, 500))
+    per = {}
+    for fam, name in FAMILIES.items():
+        ms, n = ctx.kernel_time_ms(fam)
+        if n:
+            per[name] = round(ms / n * 1e3, 2)
+    ctx.enable_timing(False)
+    flops = 2.0 * wl.N * wl.J * wl.D
+    us = per["reconstruct-apply"]
+    achieved = flops / (us * 1e-6) / 1e12
+    out = {"metric": "sfb_samples_per_sec", "value": wl.N * args.steps / elapsed, "unit": "samples/s",
+           "steps_per_sec": args.steps / elapsed, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{wl.name}: SDCA on l2-regularised MLR, J={wl.J} D={wl.D} n_data={wl.n_data} "
+                                  f"P={wl.P} B={wl.B} lam={wl.lam} s={s}", "plan": ctx.plan_info(), "launch": "eager"},
+           "roofline": {"bound": "mfma", "kernel": "reconstruct-apply", "achieved": achieved,
+                        "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                        "traffic": None, "algorithmic_flops": flops, "us_per_launch": us, "kernels_us": per}}
+    if args.cpu_seconds > 0:
+        from oracle.sdca_oracle import SdcaMlrOracle
+        o = SdcaMlrOracle(wl.A, wl.y, wl.J, wl.lam)
+        o.step_matrix(wl.pick(0), s)
+        n, t1 = 0, time.perf_counter()
+        while True:
+            o.step_matrix(wl.pick(n + 1), s)
+            n += 1
+            el = time.perf_counter() - t1
+            if el >= args.cpu_seconds or n >= 200:
+                break
+        out["cpu_baseline"] = {"value": wl.N * n / el, "unit": "samples/s", "cores": len(os.sched_getaffinity(0)),
+                               "kind": "oracle", "sample": f"{n} fp64 numpy SDCA oracle iterations of {wl.name}, {el:.2f} s"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -82,6 +158,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+    if args.config.startswith("sdca"):
+        return bench_sdca(args)
     dev = "cuda:0"
     wl = workloads.make(args.config)
     ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
