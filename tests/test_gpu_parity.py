@@ -435,3 +435,13 @@ def test_random_shapes_through_the_default_plan(sfb, model, J, D, P, B, pad, see
         over["density"] = max(0.05, 1.5 / D)
     wl = workloads.make(name, seed=seed, **over)
     run_chain(wl, 2, TOL32, pad=pad, dml_guard=1e-6)
+
+
+@pytest.mark.parametrize("name,over", [("mlr_medium", dict(J=256, D=512, P=80, B=50)),
+                                       ("dml", dict(J=64, D=256, P=32, B=128)),
+                                       ("l2svm", dict(J=128, D=1024, P=64, B=64, density=0.02))])
+def test_many_workers_and_long_contractions(sfb, name, over):
+    """N = P*B of 4000-4096 factor pairs (125-128 stages of the reconstruction ring), more than
+    64 workers (no mask is involved, so the 64-worker limit of the mask does not apply)."""
+    wl = workloads.make(name, seed=5, steps=2, pool=2, **over)
+    run_chain(wl, 2, TOL32, dml_guard=1e-6)
