@@ -391,14 +391,24 @@ sfb_status sfb_sdca_step(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* bat
     return recon_launch(c, W, ldw, U, ldu, V, ldv, 1.0f, scale, nullptr);
 }
 
-sfb_status sfb_prox(sfb_ctx* c, float* W, int64_t ldw, sfb_prox_kind kind, float eta, float param) {
-    if (!c || !W) return SFB_EINVAL;
+// kind and parameters of a proximal step; the workspace only matters for the column projection
+static sfb_status check_prox(const sfb_ctx* c, sfb_prox_kind kind, float eta, float param, bool need_workspace) {
     if ((int)kind < SFB_PROX_NONE || (int)kind > SFB_PROX_COLUMN_BALL) return SFB_EINVAL;
     if (!std::isfinite(eta) || !std::isfinite(param) || eta < 0.f || param < 0.f) return SFB_EINVAL;
     if (kind == SFB_PROX_COLUMN_BALL && !(param > 0.f)) return SFB_EINVAL;
+    if (need_workspace && kind == SFB_PROX_COLUMN_BALL && (c->ws == nullptr || c->ws_bytes < workspace_need(c)))
+        return SFB_EWORKSPACE;
+    return SFB_OK;
+}
+
+sfb_status sfb_prox(sfb_ctx* c, float* W, int64_t ldw, sfb_prox_kind kind, float eta, float param) {
+    if (!c || !W) return SFB_EINVAL;
+    sfb_status s = check_prox(c, kind, eta, param, false);
+    if (s != SFB_OK) return s;
     if (ldw < c->D) return SFB_ESHAPE;
     if (kind == SFB_PROX_NONE) return SFB_OK;
-    if (kind == SFB_PROX_COLUMN_BALL && (c->ws == nullptr || c->ws_bytes < workspace_need(c))) return SFB_EWORKSPACE;
+    s = check_prox(c, kind, eta, param, true);
+    if (s != SFB_OK) return s;
     ProxArgs a{W, ldw, (int)c->J, (int)c->D, (int)kind, eta, param};
     Timed t(c, 4);
     hipError_t e = launch_prox(a, c->ws, c->stream);
@@ -419,14 +429,6 @@ static sfb_status recon_then_prox(sfb_ctx* c, float* W, int64_t ldw, const float
     return sfb_prox(c, W, ldw, kind, eta, param);
 }
 
-static sfb_status check_prox(const sfb_ctx* c, sfb_prox_kind kind, float eta, float param) {
-    if ((int)kind < SFB_PROX_NONE || (int)kind > SFB_PROX_COLUMN_BALL) return SFB_EINVAL;
-    if (!std::isfinite(eta) || !std::isfinite(param) || eta < 0.f || param < 0.f) return SFB_EINVAL;
-    if (kind == SFB_PROX_COLUMN_BALL && !(param > 0.f)) return SFB_EINVAL;
-    if (kind == SFB_PROX_COLUMN_BALL && (c->ws == nullptr || c->ws_bytes < workspace_need(c))) return SFB_EWORKSPACE;
-    return SFB_OK;
-}
-
 sfb_status sfb_reconstruct_apply_prox(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64_t ldu, const void* V,
                                       int64_t ldv, float eta, float scale, const uint8_t* active,
                                       sfb_prox_kind kind, float param) {
@@ -434,7 +436,7 @@ sfb_status sfb_reconstruct_apply_prox(sfb_ctx* c, float* W, int64_t ldw, const f
     if (s != SFB_OK) return s;
     s = check_recon(c, eta, scale, active);
     if (s != SFB_OK) return s;
-    s = check_prox(c, kind, eta, param);
+    s = check_prox(c, kind, eta, param, true);
     if (s != SFB_OK) return s;
     return recon_then_prox(c, W, ldw, U, ldu, V, ldv, eta, scale, active, kind, param);
 }
@@ -449,7 +451,7 @@ sfb_status sfb_step_prox(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* bat
     const float scale = 1.0f / (float)c->B;
     s = check_recon(c, eta, scale, active);
     if (s != SFB_OK) return s;
-    s = check_prox(c, kind, eta, param);
+    s = check_prox(c, kind, eta, param, true);
     if (s != SFB_OK) return s;
     s = factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss);
     if (s != SFB_OK) return s;
