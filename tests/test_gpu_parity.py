@@ -445,3 +445,32 @@ def test_many_workers_and_long_contractions(sfb, name, over):
     64 workers (no mask is involved, so the 64-worker limit of the mask does not apply)."""
     wl = workloads.make(name, seed=5, steps=2, pool=2, **over)
     run_chain(wl, 2, TOL32, dml_guard=1e-6)
+
+
+@pytest.mark.parametrize("dense_scores", [False, True])
+def test_csr_worker_calls_address_the_shared_arrays_through_their_row_pointers(sfb, dense_scores):
+    """A worker's share of a CSR batch handed over without copying: the slice rowptr[p*B : (p+1)*B + 1] of
+    the batch's row pointers (first entry non-zero for p > 0) with the batch's own col / val arrays."""
+    wl = workloads.make("l2svm", seed=3, J=68, D=300, P=4, B=9, density=0.06, steps=1, pool=1)
+    dev = "cuda:0"
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+    if dense_scores:
+        ctx.set_plan(fwd_dma=3)
+    b = wl.batch(0)
+    db, dy = to_device(wl, b, dev)
+    W = torch.from_numpy(wl.W0).to(dev)
+    U, V, loss = alloc_factors(wl, dev)
+    ctx.compute_factors(W, db, dy, U, V, loss)
+    U2, V2, loss2 = alloc_factors(wl, dev)
+    for p in (2, 0, 3, 1):
+        rp = db.rowptr[p * wl.B:(p + 1) * wl.B + 1]
+        assert p == 0 or int(rp[0]) > 0
+        share = sfb.SfbBatch(rowptr=rp, col=db.col, val=db.val)
+        ctx.compute_factors_worker(W, share, dy[p * wl.B:(p + 1) * wl.B], p, U2, V2, loss2)
+    ctx.sync()
+    Uo, Vo, fo = oracle.factors(wl.model, wl.W0, b)
+    assert torch.equal(V, V2) and np.array_equal(V.cpu().numpy(), Vo.astype(np.float32))
+    for got in (U, U2):
+        assert_close(got.cpu().numpy(), Uo, TOL32, "U")
+    assert_close(loss2.cpu().numpy(), fo, TOL32, "loss")
+    ctx.close()
