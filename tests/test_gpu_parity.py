@@ -474,3 +474,19 @@ def test_csr_worker_calls_address_the_shared_arrays_through_their_row_pointers(s
         assert_close(got.cpu().numpy(), Uo, TOL32, "U")
     assert_close(loss2.cpu().numpy(), fo, TOL32, "loss")
     ctx.close()
+
+
+@pytest.mark.parametrize("dense_scores", [False, True])
+def test_csr_columns_in_any_order_within_a_row(sfb, dense_scores):
+    """The CSR rows need not be sorted by column (the header promises it): every row's entries are
+    shuffled, the step must not change beyond rounding."""
+    wl = workloads.make("l2svm", seed=8, J=96, D=640, P=3, B=11, density=0.05, steps=2, pool=2)
+    rng = np.random.default_rng(8)
+    for b in wl.batches:
+        for r in range(wl.N):
+            lo, hi = int(b["rowptr"][r]), int(b["rowptr"][r + 1])
+            perm = rng.permutation(hi - lo)
+            b["col"][lo:hi] = b["col"][lo:hi][perm]
+            b["val"][lo:hi] = b["val"][lo:hi][perm]
+        assert np.any(np.diff(b["col"][:int(b["rowptr"][1])]) < 0)
+    run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else None)
