@@ -490,3 +490,50 @@ def test_csr_columns_in_any_order_within_a_row(sfb, dense_scores):
             b["val"][lo:hi] = b["val"][lo:hi][perm]
         assert np.any(np.diff(b["col"][:int(b["rowptr"][1])]) < 0)
     run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else None)
+
+
+def _misaligned(t, off=1):
+    """A copy of the 2-D tensor t whose rows start `off` elements into rows `off + 2` elements longer:
+    neither the base address nor the row stride keeps the 16-byte alignment of the fast paths."""
+    buf = torch.zeros((t.shape[0], t.shape[1] + off + 2), dtype=t.dtype, device=t.device)
+    view = buf[:, off:off + t.shape[1]]
+    view.copy_(t)
+    return view
+
+
+@pytest.mark.parametrize("name,over,tol", [("mlr_medium", dict(J=200, D=512, P=4, B=32), TOL32),
+                                           ("dml", dict(J=64, D=256, P=2, B=64), TOL32),
+                                           ("l2svm", dict(J=64, D=512, P=2, B=32, density=0.04), TOL32),
+                                           ("mlr_large", dict(J=300, D=1024, P=4, B=40), TOLBF)])
+def test_any_alignment_is_accepted(sfb, name, over, tol):
+    """Every dense operand starts one element past an aligned address and has a row stride that is not a
+    multiple of four elements: the kernels must take their scalar paths and still match the oracle."""
+    wl = workloads.make(name, seed=12, steps=2, pool=2, **over)
+    dev = "cuda:0"
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
+    vdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    W = _misaligned(torch.from_numpy(wl.W0).to(dev))
+    U = _misaligned(torch.zeros((wl.N, wl.J), device=dev))
+    V = _misaligned(torch.zeros((wl.N, wl.D), dtype=vdt, device=dev))
+    loss = torch.zeros(wl.N + 1, device=dev)[1:]
+    Wo = wl.W0.astype(np.float64)
+    for t in range(2):
+        b = wl.batch(t)
+        db, dy = to_device(wl, b, dev)
+        if db.a is not None:
+            db.a = _misaligned(db.a)
+        if db.a2 is not None:
+            db.a2 = _misaligned(db.a2)
+        assert W.data_ptr() % 16 != 0 and W.stride(0) % 4 != 0
+        ctx.step(W, db, dy, U, V, wl.eta, loss=loss)
+        ctx.sync()
+        Uo, Vo, Wo, fo = oracle.step(wl.model, Wo, b, wl.P, wl.B, wl.eta)
+        assert_close(U.cpu().numpy(), Uo, tol, f"U step {t}")
+        assert_close(V.float().cpu().numpy(), Vo, tol, f"V step {t}")
+        assert_close(W.cpu().numpy(), Wo, tol, f"W step {t}")
+        assert_close(loss.cpu().numpy(), fo, tol, f"loss step {t}")
+    # nothing was written outside the views
+    for view in (W, U, V):
+        base = view._base
+        assert float(base[:, 0].float().abs().max()) == 0.0 and float(base[:, view.shape[1] + 1:].float().abs().max()) == 0.0
+    ctx.close()
