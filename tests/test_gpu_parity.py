@@ -537,3 +537,31 @@ def test_any_alignment_is_accepted(sfb, name, over, tol):
         base = view._base
         assert float(base[:, 0].float().abs().max()) == 0.0 and float(base[:, view.shape[1] + 1:].float().abs().max()) == 0.0
     ctx.close()
+
+
+def test_labels_outside_the_class_range_drop_the_one_hot_term(sfb):
+    """The header documents it: class ids outside [0, J) are not detected; the one-hot term is absent,
+    so u is the plain softmax (rows sum to 1) and the loss is logsumexp(z).  Nothing else is disturbed."""
+    wl = workloads.make("mlr_tiny", seed=13, J=12, D=64, P=2, B=8)
+    dev = "cuda:0"
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+    b = wl.batch(0)
+    db, dy = to_device(wl, b, dev)
+    bad = dy.clone()
+    bad[3], bad[7] = wl.J + 5, -1
+    W = torch.from_numpy(wl.W0).to(dev)
+    U, V, loss = alloc_factors(wl, dev)
+    ctx.compute_factors(W, db, bad, U, V, loss)
+    ctx.sync()
+    Z = oracle.scores(wl.W0, b["A"])
+    fo, Uo = oracle.loss_and_u("mlr", Z, b["y"])
+    got = U.cpu().numpy()
+    for i in range(wl.N):
+        if i in (3, 7):
+            soft = np.exp(Z[i] - Z[i].max())
+            soft /= soft.sum()
+            assert_close(got[i], soft, TOL32, f"row {i}: plain softmax")
+            assert abs(float(loss[i]) - float(np.log(np.exp(Z[i]).sum()))) < 1e-5
+        else:
+            assert_close(got[i], Uo[i], TOL32, f"row {i}")
+    ctx.close()
