@@ -565,3 +565,39 @@ def test_labels_outside_the_class_range_drop_the_one_hot_term(sfb):
         else:
             assert_close(got[i], Uo[i], TOL32, f"row {i}")
     ctx.close()
+
+
+def test_two_contexts_on_two_streams_do_not_disturb_each_other(sfb):
+    """Distinct contexts are independent: steps of two models interleaved on two streams (default
+    priority), without synchronising in between, give what each gives alone."""
+    dev = "cuda:0"
+    wls = [workloads.make("mlr_medium", seed=14, J=200, D=512, P=4, B=32, steps=4, pool=2),
+           workloads.make("dml", seed=15, J=96, D=256, P=2, B=64, steps=4, pool=2)]
+
+    def setup(wl, stream):
+        with torch.cuda.stream(stream):
+            ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+            W = torch.from_numpy(wl.W0).to(dev)
+            U, V, loss = alloc_factors(wl, dev)
+            pool = [to_device(wl, b, dev) for b in wl.batches]
+        stream.synchronize()
+        return ctx, W, U, V, pool
+
+    alone = []
+    for wl in wls:
+        s = torch.cuda.Stream(device=dev)
+        ctx, W, U, V, pool = setup(wl, s)
+        for t in range(4):
+            ctx.step(W, *pool[t % 2], U, V, wl.eta)
+        ctx.sync()
+        alone.append(W.clone())
+        ctx.close()
+    streams = [torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)]
+    state = [setup(wl, s) for wl, s in zip(wls, streams)]
+    for t in range(4):
+        for (ctx, W, U, V, pool), wl in zip(state, wls):
+            ctx.step(W, *pool[t % 2], U, V, wl.eta)          # enqueue only
+    for (ctx, W, U, V, pool), want in zip(state, alone):
+        ctx.sync()
+        assert torch.equal(W, want)
+        ctx.close()
