@@ -241,3 +241,21 @@ def test_launch_plans_of_the_benchmark_shapes(lib):
             assert lib.sfb_set_plan(ctx, 0, 0, 0, v, -1) == 0
         assert lib.sfb_set_plan(ctx, 0, 0, 0, 11, -1) == -1
         lib.sfb_destroy(ctx)
+
+
+def test_measurement_aids_validate_their_arguments(lib):
+    import paper_1511_08486_amd as sfb
+    ctx = C.c_void_p()
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 8, 16, 2, 4, sfb.SFB_F32, None) == 0
+    fake = C.c_void_p(0x1000)
+    assert lib.sfb_stream_copy(ctx, fake, fake, 24) == -1                    # not a multiple of 16 bytes
+    assert lib.sfb_stream_copy(ctx, C.c_void_p(0x1008), fake, 32) == -1      # destination not 16-byte aligned
+    assert lib.sfb_stream_copy(ctx, None, fake, 32) == -1 and lib.sfb_stream_copy(None, fake, fake, 32) == -1
+    ms, n = C.c_double(-1.0), C.c_int64(-1)
+    assert lib.sfb_kernel_time_ms(ctx, 9, C.byref(ms), C.byref(n)) == -1     # no such kernel family
+    assert lib.sfb_kernel_time_ms(ctx, 0, None, C.byref(n)) == -1
+    assert lib.sfb_enable_timing(None, 1) == -1 and lib.sfb_reset_timing(None) == -1
+    assert lib.sfb_plan_info(None, None, None, None) == -1
+    assert lib.sfb_last_hip_error(ctx) == 0
+    lib.sfb_destroy(ctx)
+    lib.sfb_destroy(None)                                                     # harmless
