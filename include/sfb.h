@@ -80,7 +80,8 @@ typedef enum {
  *   L2SVM:  a = a2 = NULL; CSR with N rows and D columns: csr_rowptr [N+1] (int32, first
  *           entry is this batch's offset into csr_col/csr_val, normally 0), csr_col [nnz]
  *           in [0, D), csr_val [nnz] fp32, nnz = total stored entries.  Columns may appear
- *           in any order; a column repeated inside a row is not supported.
+ *           in any order; a column repeated inside a row counts as the sum of its values
+ *           (in the scores and in the dense row v_i alike).
  */
 typedef struct sfb_batch {
     const void *a;
@@ -237,6 +238,11 @@ SFB_API sfb_status sfb_step_prox(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_
 SFB_API sfb_status sfb_shape(const sfb_ctx *ctx, int64_t *J, int64_t *D, int32_t *P, int32_t *B,
                      int32_t *input_dtype);
 
+/* The scale sfb_step uses: 1/B as fp32, the mean over a worker's K = B samples (Section 3,
+ * mini-batch paragraph).  Callers of sfb_reconstruct_apply that want the same update as
+ * sfb_step pass this value. */
+SFB_API sfb_status sfb_default_scale(const sfb_ctx *ctx, float *scale);
+
 /* hipStreamSynchronize on the context's stream; SFB_EHIP if the stream reports an error. */
 SFB_API sfb_status sfb_sync(sfb_ctx *ctx);
 
@@ -299,6 +305,8 @@ SFB_API sfb_status sfb_reset_timing(sfb_ctx *ctx);
  * rules bound t_q - tau[p][q] by 2*staleness + 2: q is at most staleness + 1 ahead of p, and p
  * at most staleness + 1 ahead of what it has applied of q).  Each set is applied with the eta of the
  * iteration that produced it and scale 1/B.
+ * If a kernel launch fails in the middle of an event (SFB_EHIP), the replicas and the clocks no
+ * longer describe the same state: that status is returned by every later event of the simulator.
  *   W_replicas  HOST array of P DEVICE pointers, each [J][ldw] fp32.
  *   U_ring      DEVICE [ring_slots][N][ldu] fp32;  V_ring  DEVICE [ring_slots][N][ldv] in the
  *               context's dtype.  The ctx must outlive the simulator; its workspace must be set.

@@ -195,12 +195,10 @@ def delta_w(U, V, P, B, active=None):
     if U.shape[0] != P * B or V.shape[0] != P * B:
         raise ValueError("U and V must have P*B rows")
     live = _live(P, active)
-    dW = np.zeros((U.shape[1], V.shape[1]), dtype=_F)
-    for p in range(P):
-        if live[p]:
-            rows = slice(p * B, (p + 1) * B)
-            dW += (U[rows].T @ V[rows]) / B
-    return dW
+    # every sample's outer product u v^T enters with weight 1/B if its worker is live and 0
+    # otherwise: scale the rows of U by that weight, then sum the outer products (U^T V)
+    weight = np.repeat(np.where(live, 1.0 / B, 0.0), B)
+    return (U * weight[:, None]).T @ V
 
 
 # --------------------------------------------------------------------------

@@ -53,6 +53,7 @@ def _load():
         "sfb_compute_factors_worker": (C.c_int, [vp, vp, i64, pb, vp, i32, vp, i64, vp, i64, vp]),
         "sfb_reconstruct_apply": (C.c_int, [vp, vp, i64, vp, i64, vp, i64, f32, f32, vp]),
         "sfb_step": (C.c_int, [vp, vp, i64, pb, vp, vp, i64, vp, i64, vp, f32, vp]),
+        "sfb_default_scale": (C.c_int, [vp, C.POINTER(f32)]),
         "sfb_sync": (C.c_int, [vp]),
         "sfb_strerror": (C.c_char_p, [C.c_int]),
         "sfb_last_hip_error": (C.c_int, [vp]),
@@ -188,6 +189,12 @@ class Sfb:
                                                    V.data_ptr(), V.stride(0), _ptr(loss)),
                     "sfb_compute_factors_worker")
 
+    def default_scale(self):
+        """1/B as the library's fp32 (what sfb_step passes to the reconstruction)."""
+        v = C.c_float()
+        self._check(lib.sfb_default_scale(self._ctx, C.byref(v)), "sfb_default_scale")
+        return v.value
+
     @staticmethod
     def _mask(active):
         if active is None:
@@ -197,7 +204,7 @@ class Sfb:
 
     def reconstruct_apply(self, W, U, V, eta, scale=None, active=None):
         if scale is None:
-            scale = 1.0 / self.B
+            scale = self.default_scale()
         if active is not None and len(active) != self.P:
             raise ValueError("active mask must have P entries")
         keep, ptr = self._mask(active)
@@ -207,7 +214,7 @@ class Sfb:
 
     def reconstruct_apply_worker(self, W, U, V, p, eta, scale=None):
         if scale is None:
-            scale = 1.0 / self.B
+            scale = self.default_scale()
         self._check(lib.sfb_reconstruct_apply_worker(self._ctx, W.data_ptr(), W.stride(0), U.data_ptr(), U.stride(0),
                                                      V.data_ptr(), V.stride(0), int(p), float(eta), float(scale)),
                     "sfb_reconstruct_apply_worker")
@@ -230,7 +237,7 @@ class Sfb:
 
     def reconstruct_apply_prox(self, W, U, V, eta, kind, param, scale=None, active=None):
         if scale is None:
-            scale = 1.0 / self.B
+            scale = self.default_scale()
         keep, ptr = self._mask(active)
         self._check(lib.sfb_reconstruct_apply_prox(self._ctx, W.data_ptr(), W.stride(0), U.data_ptr(), U.stride(0),
                                                    V.data_ptr(), V.stride(0), float(eta), float(scale), ptr,

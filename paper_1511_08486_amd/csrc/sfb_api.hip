@@ -92,9 +92,17 @@ struct Timed {
         if (!c->spare.empty()) {
             ev = c->spare.back();
             c->spare.pop_back();
-        } else if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) {
-            on = false;
-            return;
+        } else {
+            hipError_t e = hipEventCreate(&ev.a);
+            if (e == hipSuccess) {
+                e = hipEventCreate(&ev.b);
+                if (e != hipSuccess) (void)hipEventDestroy(ev.a);
+            }
+            if (e != hipSuccess) {          // this launch goes untimed; the caller can see why
+                c->last_hip = (int)e;
+                on = false;
+                return;
+            }
         }
         LaunchEvents& le = launch_events();
         le.start = ev.a;
@@ -360,7 +368,8 @@ sfb_status sfb_step(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, c
     if (s != SFB_OK) return s;
     s = check_batch(c, batch, y);
     if (s != SFB_OK) return s;
-    const float scale = 1.0f / (float)c->B;   // mini-batch mean inside a worker (Section 3)
+    float scale;                              // mini-batch mean inside a worker (Section 3)
+    (void)sfb_default_scale(c, &scale);
     s = check_recon(c, eta, scale, active);
     if (s != SFB_OK) return s;
     s = factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss);
@@ -448,7 +457,8 @@ sfb_status sfb_step_prox(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* bat
     if (s != SFB_OK) return s;
     s = check_batch(c, batch, y);
     if (s != SFB_OK) return s;
-    const float scale = 1.0f / (float)c->B;
+    float scale;
+    (void)sfb_default_scale(c, &scale);
     s = check_recon(c, eta, scale, active);
     if (s != SFB_OK) return s;
     s = check_prox(c, kind, eta, param, true);
@@ -465,6 +475,12 @@ sfb_status sfb_shape(const sfb_ctx* c, int64_t* J, int64_t* D, int32_t* P, int32
     if (P) *P = c->P;
     if (B) *B = c->B;
     if (input_dtype) *input_dtype = (int32_t)c->dtype;
+    return SFB_OK;
+}
+
+sfb_status sfb_default_scale(const sfb_ctx* c, float* scale) {
+    if (!c || !scale) return SFB_EINVAL;
+    *scale = 1.0f / (float)c->B;
     return SFB_OK;
 }
 
@@ -495,7 +511,7 @@ sfb_status sfb_plan_info(const sfb_ctx* c, int32_t* fwd_split_k, int32_t* fwd_gr
     const FwdPlan& f = c->dtype == SFB_BF16 ? c->fwd_bf16 : c->fwd_all;
     if (fwd_split_k) *fwd_split_k = f.split_k;
     if (fwd_grid) *fwd_grid = f.grid;
-    if (recon_grid) *recon_grid = c->recon.grid;
+    if (recon_grid) *recon_grid = c->dtype == SFB_BF16 ? bf16_recon_grid(c->J, c->D) : c->recon.grid;
     return SFB_OK;
 }
 

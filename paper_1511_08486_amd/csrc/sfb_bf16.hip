@@ -340,6 +340,10 @@ size_t bf16_recon_workspace(int64_t J, int64_t D, int64_t N) {
     return up((size_t)J * ldn * 2) + up((size_t)D * ldn * 2);
 }
 
+int bf16_recon_grid(int64_t J, int64_t D) {
+    return (int)(((J + kBfReconBM - 1) / kBfReconBM) * ((D + kBfReconBN - 1) / kBfReconBN));
+}
+
 hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s) {
     const int64_t ldn = bf16_ldn(a.N);
     auto up = [](size_t b) { return (b + 255) / 256 * 256; };
@@ -355,7 +359,7 @@ hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s) 
     constexpr int NST = 3, BK = kBfReconBK, WPS = kBfReconWPS;
     constexpr int BM = kBfReconBM, BN = kBfReconBN;
     constexpr size_t lds_bytes = (size_t)NST * (BM + BN) * (BK / 8) * 16;
-    static bool raised = false;
+    static std::atomic<bool> raised{false};
     if (lds_bytes > 64 * 1024 && !raised) {
         e = hipFuncSetAttribute((const void*)nt_bf16_kernel<false, kUpdateW, NST, BK, WPS, BM, BN, 2, 2>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -411,7 +415,7 @@ FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D) {
 hipError_t launch_forward_bf16(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
     constexpr int NST = 3, BK = kBfFwdBK, BM = kBfFwdBM, BN = kBfFwdBN;
     constexpr size_t lds_bytes = (size_t)NST * (BM * (BK / 8) + BN * (BK / 4)) * 16;
-    static bool raised = false;
+    static std::atomic<bool> raised{false};
     if (lds_bytes > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute((const void*)nt_bf16_kernel<true, kStoreZ, NST, BK, 2, BM, BN, 4, 2>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);

@@ -395,7 +395,7 @@ static hipError_t launch_fwd_dma(const FwdArgs& a, const FwdPlan& p, hipStream_t
     const int n_nb = (a.n_rows + BM - 1) / BM, n_jb = (a.J + BN - 1) / BN;
     const int total = n_nb * n_jb * p.split_k;
     constexpr size_t lds_bytes = kFwdDmaStages * (BM + BN + (DIFF ? BM : 0)) * kFwdBK * sizeof(float);
-    static bool raised = false;
+    static std::atomic<bool> raised{false};
     if (lds_bytes > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute((const void*)fwd_scores_dma_kernel<BM, BN, DIFF>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -464,7 +464,7 @@ static hipError_t launch_fwd_f(const FwdArgs& a, const FwdPlan& p, hipStream_t s
     const int n_nb = (a.n_rows + BM - 1) / BM, n_jb = (a.J + BN - 1) / BN;
     const int total = n_nb * n_jb * p.split_k;
     constexpr size_t lds_bytes = 2 * (BM + BN) * kFwdLds * sizeof(float);
-    static bool raised = false;   // opt in once to more than 64 KB of LDS per workgroup
+    static std::atomic<bool> raised{false};   // opt in once to more than 64 KB of LDS per workgroup
     if (lds_bytes > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute((const void*)fwd_scores_kernel<BM, BN, TIn, DIFF, FAST>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);

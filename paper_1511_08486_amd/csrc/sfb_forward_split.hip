@@ -225,7 +225,7 @@ bool forward_split_ok(const FwdArgs& a) {
 template <bool DIFF>
 static hipError_t launch_split(const FwdArgs& a, const FwdPlan& p, hipStream_t s) {
     constexpr size_t lds_bytes = 2 * (size_t)kSsStageBytes;
-    static bool raised = false;
+    static std::atomic<bool> raised{false};
     if (!raised) {
         hipError_t e = hipFuncSetAttribute((const void*)scores_split_kernel<DIFF>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);

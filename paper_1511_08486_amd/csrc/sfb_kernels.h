@@ -6,6 +6,8 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace sfb {
 
 enum Model { kMLR = 0, kDML = 1, kL2SVM = 2 };
@@ -154,6 +156,7 @@ bool forward_bf16_ok(const FwdArgs& a);                       // alignment / sha
 FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D);
 hipError_t launch_forward_bf16(const FwdArgs& a, const FwdPlan& p, hipStream_t s);
 size_t bf16_recon_workspace(int64_t J, int64_t D, int64_t N);  // bytes of device scratch
+int bf16_recon_grid(int64_t J, int64_t D);                     // workgroups of the W += C launch
 // ws: bf16_recon_workspace bytes, 256-byte aligned.  Two launches: transpose/pack, then W += C.
 hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s);
 

@@ -518,7 +518,7 @@ static hipError_t launch_recon_dma(const ReconArgs& a, hipStream_t s) {
     const int n_jb = (a.J + BM - 1) / BM, n_db = a.D / kReconBN;
     const int total = n_jb * n_db;
     constexpr size_t lds_bytes = (size_t)NST * BK * (BM + kReconBN) * sizeof(float);
-    static bool raised = false;
+    static std::atomic<bool> raised{false};
     if (lds_bytes > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_dma_kernel<MT, NWR, BK, NST, WPS>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -609,7 +609,7 @@ static hipError_t launch_recon_f(const ReconArgs& a, hipStream_t s, bool vec_w, 
     const int n_jb = (a.J + BM - 1) / BM, n_db = (a.D + kReconBN - 1) / kReconBN;
     const int total = n_jb * n_db;
     constexpr size_t lds_bytes = 2 * kReconBK * (BM + kReconBN) * sizeof(float);
-    static bool raised = false;   // opt in once to more than 64 KB of LDS per workgroup
+    static std::atomic<bool> raised{false};   // opt in once to more than 64 KB of LDS per workgroup
     if (lds_bytes > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_kernel<MT, NWR, KS, TV, FAST, MASK>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);

@@ -182,7 +182,7 @@ bool reconstruct_split_ok(const ReconArgs& a) {
 
 hipError_t launch_reconstruct_split(const ReconArgs& a, hipStream_t s) {
     constexpr size_t lds_bytes = 2 * (size_t)kRsStageBytes;
-    static bool raised = false;
+    static std::atomic<bool> raised{false};
     if (!raised) {
         hipError_t e = hipFuncSetAttribute((const void*)reconstruct_split_kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);

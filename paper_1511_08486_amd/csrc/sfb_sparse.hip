@@ -8,9 +8,12 @@ namespace sfb {
 
 constexpr int kDensifyThreads = 256;
 
-// One workgroup per sample: zero the row with wide stores, then scatter the stored
-// entries.  The barrier orders the two phases inside the workgroup, and no other
-// workgroup touches this row.
+// One workgroup per sample: zero the row with wide stores, then add the stored entries
+// into it.  The barrier orders the two phases inside the workgroup, and no other
+// workgroup touches this row.  Entries are ADDED (hardware fp32 atomic), so a column that
+// appears more than once in a row contributes the sum of its values, exactly as it does in
+// the scores computed from the stored entries; a column that appears once lands bit for bit
+// (0 + v = v).  With three or more repeats the order of the additions is not fixed.
 __global__ __launch_bounds__(kDensifyThreads) void csr_densify_kernel(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ col, const float* __restrict__ val,
     float* __restrict__ V, int64_t ldv, int D, int64_t nnz, bool vec_v) {
@@ -24,7 +27,7 @@ __global__ __launch_bounds__(kDensifyThreads) void csr_densify_kernel(
     const int64_t end = min((int64_t)rowptr[row + 1], nnz);
     for (int64_t n = beg + threadIdx.x; n < end; n += kDensifyThreads) {
         const int c = col[n];
-        if (c >= 0 && c < D) out[c] = val[n];
+        if (c >= 0 && c < D) unsafeAtomicAdd(out + c, val[n]);
     }
 }
 
@@ -212,7 +215,7 @@ bool csr_scores_ok(int D) { return (size_t)D * kSpRows * sizeof(float) <= 160 * 
 hipError_t launch_csr_scores(const DensifyArgs& a, const float* W, int64_t ldw, float* Z, int64_t ldz, int J,
                              hipStream_t s) {
     const size_t lds_bytes = (size_t)a.D * kSpRows * sizeof(float);
-    static size_t raised = 0;   // largest LDS size opted in to so far
+    static std::atomic<size_t> raised{0};   // largest LDS size opted in to so far
     if (lds_bytes > 64 * 1024 && lds_bytes > raised) {
         hipError_t e = hipFuncSetAttribute((const void*)csr_scores_kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);

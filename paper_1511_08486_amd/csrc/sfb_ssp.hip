@@ -21,6 +21,8 @@ struct sfb_ssp {
     std::vector<int32_t> tau;            // [P][P] sets of q applied at replica p
     std::vector<float> eta;              // [slots][P] step size of the set held in that slot
     std::vector<uint8_t> sends;          // [P][P] sends[q * P + p] != 0: worker q's factors go to replica p
+    sfb_status broken;                   // a launch failed after part of an event was enqueued: the replicas and
+                                         // the clocks no longer describe the same state, every later event is refused
 };
 
 namespace {
@@ -62,6 +64,7 @@ sfb_status sfb_ssp_create(sfb_ssp** out, sfb_ctx* ctx, int32_t staleness, float*
     s->tau.assign((size_t)P * P, 0);
     s->eta.assign((size_t)ring_slots * P, 0.f);
     s->sends.assign((size_t)P * P, 1);   // full broadcast
+    s->broken = SFB_OK;
     *out = s;
     return SFB_OK;
 }
@@ -71,6 +74,7 @@ void sfb_ssp_destroy(sfb_ssp* s) { delete s; }
 sfb_status sfb_ssp_worker_step(sfb_ssp* s, int32_t p, const sfb_batch* batch_p, const int32_t* y_p, float eta,
                                float* loss, int32_t* blocked) {
     if (!s || !blocked) return SFB_EINVAL;
+    if (s->broken != SFB_OK) return s->broken;
     if (p < 0 || p >= s->P) return SFB_ESHAPE;
     const int32_t P = s->P, c = s->t[p];
     for (int32_t q = 0; q < P; ++q) {
@@ -90,10 +94,13 @@ sfb_status sfb_ssp_worker_step(sfb_ssp* s, int32_t p, const sfb_batch* batch_p, 
     float* U = u_slot(s, c);
     void* V = v_slot(s, c);
     sfb_status st = sfb_compute_factors_worker(s->ctx, s->W[p], s->ldw, batch_p, y_p, p, U, s->ldu, V, s->ldv, loss);
-    if (st != SFB_OK) return st;
-    const float scale = 1.0f / (float)s->B;   // mini-batch mean inside a worker (Section 3)
+    // validation errors come back before anything is launched; a failed launch may have left part of the
+    // factors in the ring slot
+    if (st != SFB_OK) return st == SFB_EHIP ? (s->broken = st) : st;
+    float scale;                              // mini-batch mean inside a worker (Section 3)
+    (void)sfb_default_scale(s->ctx, &scale);
     st = sfb_reconstruct_apply_worker(s->ctx, s->W[p], s->ldw, U, s->ldu, V, s->ldv, p, eta, scale);
-    if (st != SFB_OK) return st;
+    if (st != SFB_OK) return s->broken = st;  // the factors are in the ring but the worker's own update is not applied
     s->eta[(size_t)(c % s->slots) * P + p] = eta;
     s->t[p] = c + 1;
     s->tau[(size_t)p * P + p] = c + 1;
@@ -102,6 +109,7 @@ sfb_status sfb_ssp_worker_step(sfb_ssp* s, int32_t p, const sfb_batch* batch_p, 
 
 sfb_status sfb_ssp_deliver(sfb_ssp* s, int32_t p, int32_t q, int32_t count) {
     if (!s) return SFB_EINVAL;
+    if (s->broken != SFB_OK) return s->broken;
     if (p < 0 || p >= s->P || q < 0 || q >= s->P) return SFB_ESHAPE;
     if (p == q || count < 0) return SFB_EINVAL;
     const int32_t P = s->P;
@@ -109,11 +117,12 @@ sfb_status sfb_ssp_deliver(sfb_ssp* s, int32_t p, int32_t q, int32_t count) {
     const int32_t have = s->tau[(size_t)p * P + q];
     if (have + count > s->t[q]) return SFB_EINVAL;     // q has not produced that many
     if (have + count > s->t[p]) return SFB_EINVAL;     // no fast-forward
-    const float scale = 1.0f / (float)s->B;
+    float scale;
+    (void)sfb_default_scale(s->ctx, &scale);
     for (int32_t it = have; it < have + count; ++it) {
         sfb_status st = sfb_reconstruct_apply_worker(s->ctx, s->W[p], s->ldw, u_slot(s, it), s->ldu, v_slot(s, it),
                                                      s->ldv, q, s->eta[(size_t)(it % s->slots) * P + q], scale);
-        if (st != SFB_OK) return st;
+        if (st != SFB_OK) return s->broken = st;   // sets before `it` are applied and counted, this one is not
         s->tau[(size_t)p * P + q] = it + 1;
     }
     return SFB_OK;

@@ -55,9 +55,47 @@ def alloc_factors(wl, dev="cuda:0", pad_u=0, pad_v=0, fill=float("nan")):
     return U, V, loss
 
 
-def run_chain(wl, steps, tol, check_every=1, dml_guard=2e-5, pad=0, plan=None):
+def fresh_update(ctx, U, V, eta, like, scale=None, active=None):
+    """-eta * scale * U^T V as the library's reconstruction forms it, applied to a zero matrix shaped
+    and strided like `like`: the update itself, not hidden behind the much larger entries of W."""
+    Z = torch.zeros_like(like._base if like._base is not None else like)
+    if like._base is not None:
+        Z = Z[:, :like.shape[1]]
+    ctx.reconstruct_apply(Z, U, V, eta, scale=scale, active=active)
+    ctx.sync()
+    return Z
+
+
+def make_clear_of_kink(name, seed, chain_steps, guard=1e-4, **over):
+    """workloads.make(name, seed=s, **over) for the first s >= seed whose metric-learning chain keeps
+    every dissimilar pair further than `guard` from the hinge kink |z|^2 = 1 during `chain_steps` oracle steps
+    (inside that band an fp32 path may legitimately take the other branch, so such inputs decide
+    nothing).  Decided by the oracle alone, on the CPU; other models are returned as they are."""
+    for s in range(seed, seed + 64):
+        wl = workloads.make(name, seed=s, **over)
+        if wl.model != "dml":
+            return wl
+        W = wl.W0.astype(np.float64)
+        clear = True
+        for t in range(chain_steps):
+            b = wl.batch(t)
+            _, Vo, W_new, _ = oracle.step(wl.model, W, b, wl.P, wl.B, wl.eta)
+            if oracle.dml_margin_distance(oracle.scores(W, Vo), b["y"]) <= guard:
+                clear = False
+                break
+            W = W_new
+        if clear:
+            return wl
+    raise AssertionError("no seed keeps the chain clear of the hinge kink")
+
+
+def run_chain(wl, steps, tol, check_every=1, dml_guard=1e-4, pad=0, plan=None, progress=None):
     """Runs `steps` SFB steps on the GPU and in the oracle from the same W0 and batches and
-    compares U, V, W and the per-sample loss after every step."""
+    compares U, V, W, the per-sample loss and the update -eta*dW itself after every checked step.
+    (W alone would not pin the reconstruction: one step's update is far below tol * |W| for most
+    entries, so the same factors are also applied to a zero matrix and compared with the oracle's
+    W_new - W.)  `progress` (optional) is called with a line of text after every step: long chains
+    report through it so that a watcher of the run's output sees them advance."""
     import paper_1511_08486_amd as sfb
     dev = "cuda:0"
     ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
@@ -68,7 +106,7 @@ def run_chain(wl, steps, tol, check_every=1, dml_guard=2e-5, pad=0, plan=None):
     U, V, loss = alloc_factors(wl, dev, pad_u=pad, pad_v=pad)
     Wo = wl.W0.astype(np.float64)
     dev_batches = [to_device(wl, b, dev) for b in wl.batches]
-    worst = {"U": 0.0, "V": 0.0, "W": 0.0, "loss": 0.0}
+    worst = {"U": 0.0, "V": 0.0, "W": 0.0, "loss": 0.0, "dW": 0.0}
     for t in range(steps):
         b = wl.batch(t)
         db, dy = dev_batches[t % len(dev_batches)]
@@ -78,11 +116,18 @@ def run_chain(wl, steps, tol, check_every=1, dml_guard=2e-5, pad=0, plan=None):
         if wl.model == "dml":
             margin = oracle.dml_margin_distance(oracle.scores(Wo, Vo), b["y"])
             assert margin > dml_guard, f"step {t}: a dissimilar pair sits {margin:.2e} from the hinge kink"
+        checked = t % check_every == 0 or t == steps - 1
+        upd_o = (Wo_new - Wo) if checked else None          # -eta * dW of the oracle
         Wo = Wo_new
-        if t % check_every == 0 or t == steps - 1:
+        if checked:
             worst["U"] = max(worst["U"], assert_close(U.cpu().numpy(), Uo, tol, f"U step {t}"))
             worst["V"] = max(worst["V"], assert_close(V.float().cpu().numpy(), Vo, tol, f"V step {t}"))
             worst["W"] = max(worst["W"], assert_close(Wg.cpu().numpy(), Wo, tol, f"W step {t}"))
             worst["loss"] = max(worst["loss"], assert_close(loss.cpu().numpy(), fo, tol, f"loss step {t}"))
+            upd_g = fresh_update(ctx, U, V, wl.eta, Wg)
+            worst["dW"] = max(worst["dW"], assert_close(upd_g.cpu().numpy(), upd_o, tol, f"-eta*dW step {t}"))
+            del upd_g, upd_o
+        if progress:
+            progress(f"{wl.name}: step {t + 1}/{steps}" + (f" checked, worst error/allowance so far {worst}" if checked else ""))
     ctx.close()
     return worst

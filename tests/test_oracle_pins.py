@@ -290,6 +290,20 @@ def test_csr_expansion_matches_scipy():
     np.testing.assert_array_equal(ref, b["_dense"])
 
 
+def test_csr_column_repeated_inside_a_row_counts_as_the_sum_of_its_values():
+    """A stored entry is a term of the sparse vector: two entries on one column add up (what scipy's
+    CSR does as well), in any order of the entries."""
+    import scipy.sparse
+    rowptr = np.array([0, 4, 4, 7], dtype=np.int32)
+    col = np.array([5, 1, 5, 0, 2, 2, 2], dtype=np.int32)
+    val = np.array([0.5, -1.0, 0.25, 2.0, 1.0, 2.0, 4.0], dtype=np.float32)
+    got = oracle.csr_to_dense(rowptr, col, val, 6)
+    want = np.zeros((3, 6))
+    want[0, 5], want[0, 1], want[0, 0], want[2, 2] = 0.75, -1.0, 2.0, 7.0
+    np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(got, scipy.sparse.csr_matrix((val, col, rowptr), shape=(3, 6)).toarray())
+
+
 # ---- planted mistakes: each plausible slip must trip the autograd pin ----
 def _autograd_pin_holds(model="mlr"):
     try:
