@@ -7,8 +7,11 @@ import oracle
 import workloads
 
 
-def close(got, want, tol, floor=1e-2):
+def close(got, want, tol, floor=1e-2, terms=None):
     """|got - want| <= tol * max(|want|, floor * max|want|), element by element.
+    With `terms` (same shape: for a sum, the sum of the magnitudes of its terms) the allowance is
+    tol * max(|want|, floor * max|want|, terms): an entry whose terms cancel is held to the size of
+    what was added up, the componentwise bound of a rounded inner product.
     Returns (ok, worst ratio of error to allowance)."""
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
@@ -16,8 +19,10 @@ def close(got, want, tol, floor=1e-2):
     if want.size == 0:
         return True, 0.0
     scale = np.abs(want).max()
-    allow = tol * np.maximum(np.abs(want), floor * scale)
-    allow = np.maximum(allow, 1e-30)
+    allow = np.maximum(np.abs(want), floor * scale)
+    if terms is not None:
+        allow = np.maximum(allow, np.asarray(terms, dtype=np.float64))
+    allow = np.maximum(tol * allow, 1e-30)
     err = np.abs(got - want)
     if not np.all(np.isfinite(got)):
         return False, float("inf")
@@ -25,8 +30,8 @@ def close(got, want, tol, floor=1e-2):
     return worst <= 1.0, worst
 
 
-def assert_close(got, want, tol, what):
-    ok, worst = close(got, want, tol)
+def assert_close(got, want, tol, what, terms=None):
+    ok, worst = close(got, want, tol, terms=terms)
     assert ok, f"{what}: error is {worst:.3g} x the allowance (tol {tol})"
     return worst
 
@@ -125,8 +130,10 @@ def run_chain(wl, steps, tol, check_every=1, dml_guard=1e-4, pad=0, plan=None, p
             worst["W"] = max(worst["W"], assert_close(Wg.cpu().numpy(), Wo, tol, f"W step {t}"))
             worst["loss"] = max(worst["loss"], assert_close(loss.cpu().numpy(), fo, tol, f"loss step {t}"))
             upd_g = fresh_update(ctx, U, V, wl.eta, Wg)
-            worst["dW"] = max(worst["dW"], assert_close(upd_g.cpu().numpy(), upd_o, tol, f"-eta*dW step {t}"))
-            del upd_g, upd_o
+            # sum of the magnitudes of every entry's terms, eta/B * sum_i |u_i| |v_i|^T, from the oracle's factors
+            mag = wl.eta * oracle.delta_w(np.abs(Uo), np.abs(Vo), wl.P, wl.B)
+            worst["dW"] = max(worst["dW"], assert_close(upd_g.cpu().numpy(), upd_o, tol, f"-eta*dW step {t}", terms=mag))
+            del upd_g, upd_o, mag
         if progress:
             progress(f"{wl.name}: step {t + 1}/{steps}" + (f" checked, worst error/allowance so far {worst}" if checked else ""))
     ctx.close()

@@ -197,7 +197,8 @@ def test_bf16_dead_worker_and_plain_sum(sfb):
     assert_close(W.cpu().numpy(), want, TOLBF, "W, bf16, dead worker")
     U[wl.B:2 * wl.B] = float("nan")
     upd = fresh_update(ctx, U, V, 0.2, W, scale=1.0, active=active)
-    assert_close(upd.cpu().numpy(), want - wl.W0, TOLBF, "-eta*dW, bf16, dead worker")
+    mag = 0.2 * wl.B * oracle.delta_w(np.abs(Uo), np.abs(Vo), wl.P, wl.B, active)      # sum of |terms| (scale 1)
+    assert_close(upd.cpu().numpy(), want - wl.W0, TOLBF, "-eta*dW, bf16, dead worker", terms=mag)
     assert np.array_equal(V.float().cpu().numpy(), b["A"])
     ctx.close()
 
@@ -231,7 +232,8 @@ def test_worker_calls_equal_batched_call_and_mask_drops_a_worker(sfb):
     want = oracle.apply_update(wl.W0, oracle.delta_w(Uo, Vo, wl.P, wl.B, active) * wl.B, 0.3)
     assert_close(W1.cpu().numpy(), want, TOL32, "W with dead worker")
     upd = fresh_update(ctx, U, V, 0.3, W, scale=1.0, active=active)
-    assert_close(upd.cpu().numpy(), want - wl.W0, TOL32, "-eta*dW with dead worker")
+    mag = 0.3 * wl.B * oracle.delta_w(np.abs(Uo), np.abs(Vo), wl.P, wl.B, active)
+    assert_close(upd.cpu().numpy(), want - wl.W0, TOL32, "-eta*dW with dead worker", terms=mag)
     # a dead worker's buffers may hold anything, even NaN
     U3, V3 = U.clone(), V.clone()
     U3[2 * wl.B:3 * wl.B] = float("nan")
