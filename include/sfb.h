@@ -284,6 +284,30 @@ SFB_API sfb_status sfb_set_plan(sfb_ctx *ctx, int32_t fwd_bm, int32_t fwd_bn, in
  * SFB_EINVAL).  Gives the achievable copy bandwidth of the part and a known-size kernel for
  * calibrating hardware traffic counters.  Timed under family 3. */
 SFB_API sfb_status sfb_stream_copy(sfb_ctx *ctx, void *dst, const void *src, size_t bytes);
+/*
+ * Measurement aids, not part of the method: one launch that does only the memory traffic or only
+ * the matrix-core work of one of the path's kernels, in that kernel's access shape, on the
+ * context's stream; timed under family 3.  They give the floors the kernels are compared with.
+ *   SFB_PROBE_W_STREAM  reads W [J][ldw] once the way the bf16 score pass does (blocks of 256 rows
+ *                       walked along a slice of D, 128 bytes per row and step); param = how many
+ *                       workgroups read every block (1, or 2 = the score pass at N = 512).  W must
+ *                       be 16-byte aligned with ldw % 4 == 0 and D % 32 == 0 (else SFB_EUNSUPPORTED).
+ *   SFB_PROBE_W_RMW     W += 0 in the tile and lane mapping of the bf16 reconstruction's update
+ *                       (256 x 128 tiles, accumulator layout); W keeps its values; param ignored.
+ *   SFB_PROBE_MFMA_F32  register-resident loop of v_mfma_f32_32x32x2_f32 on every compute unit, param = 1
+ *   SFB_PROBE_MFMA_BF16 or 2 wavefronts per SIMD; 256 * 4 * param wavefronts run SFB_PROBE_MFMA_ITERS * 16
+ *                       instructions each (4096 resp. 32768 flop per instruction); W is ignored.
+ * Needs a registered workspace (64 floats of it are scribbled on).  SFB_EINVAL: null W where one is
+ * needed, param outside its range, unknown kind.
+ */
+typedef enum {
+    SFB_PROBE_W_STREAM = 0,
+    SFB_PROBE_W_RMW = 1,
+    SFB_PROBE_MFMA_F32 = 2,
+    SFB_PROBE_MFMA_BF16 = 3
+} sfb_probe_kind;
+#define SFB_PROBE_MFMA_ITERS 4000
+SFB_API sfb_status sfb_probe(sfb_ctx *ctx, sfb_probe_kind kind, float *W, int64_t ldw, int32_t param);
 SFB_API sfb_status sfb_enable_timing(sfb_ctx *ctx, int enable);
 SFB_API sfb_status sfb_kernel_time_ms(sfb_ctx *ctx, int which, double *ms, int64_t *launches);
 SFB_API sfb_status sfb_reset_timing(sfb_ctx *ctx);

@@ -60,6 +60,7 @@ def _load():
         "sfb_plan_info": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
         "sfb_set_plan": (C.c_int, [vp, i32, i32, i32, i32, i32]),
         "sfb_stream_copy": (C.c_int, [vp, vp, vp, C.c_size_t]),
+        "sfb_probe": (C.c_int, [vp, C.c_int, vp, i64, i32]),
         "sfb_enable_timing": (C.c_int, [vp, C.c_int]),
         "sfb_kernel_time_ms": (C.c_int, [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]),
         "sfb_reset_timing": (C.c_int, [vp]),
@@ -285,6 +286,14 @@ class Sfb:
     def stream_copy(self, dst, src):
         nbytes = src.numel() * src.element_size()
         self._check(lib.sfb_stream_copy(self._ctx, dst.data_ptr(), src.data_ptr(), nbytes), "sfb_stream_copy")
+
+    PROBES = {"w_stream": 0, "w_rmw": 1, "mfma_f32": 2, "mfma_bf16": 3}
+    PROBE_MFMA_ITERS = 4000
+
+    def probe(self, kind, W=None, param=1):
+        """One launch of a measurement aid (sfb_probe); time it with enable_timing / kernel_time_ms(3)."""
+        self._check(lib.sfb_probe(self._ctx, self.PROBES[kind], _ptr(W), W.stride(0) if W is not None else 0,
+                                  int(param)), "sfb_probe")
 
     def enable_timing(self, on=True):
         self._check(lib.sfb_enable_timing(self._ctx, 1 if on else 0), "sfb_enable_timing")

@@ -545,6 +545,39 @@ sfb_status sfb_stream_copy(sfb_ctx* c, void* dst, const void* src, size_t bytes)
     return SFB_OK;
 }
 
+sfb_status sfb_probe(sfb_ctx* c, sfb_probe_kind kind, float* W, int64_t ldw, int32_t param) {
+    if (!c) return SFB_EINVAL;
+    if (c->ws == nullptr || c->ws_bytes < 256) return SFB_EWORKSPACE;      // 64 floats of sink
+    hipError_t e;
+    switch (kind) {
+        case SFB_PROBE_W_STREAM: {
+            if (!W || (param != 1 && param != 2)) return SFB_EINVAL;
+            if (ldw < c->D) return SFB_ESHAPE;
+            if (((uintptr_t)W % 16) != 0 || (ldw % 4) != 0 || (c->D % 32) != 0) return SFB_EUNSUPPORTED;
+            Timed t(c, 3);
+            e = launch_probe_w_stream(W, ldw, (int)c->J, (int)c->D, c->fwd_bf16.k_slice, param, (float*)c->ws, c->stream);
+            break;
+        }
+        case SFB_PROBE_W_RMW: {
+            if (!W) return SFB_EINVAL;
+            if (ldw < c->D) return SFB_ESHAPE;
+            Timed t(c, 3);
+            e = launch_probe_w_rmw(W, ldw, (int)c->J, (int)c->D, 0.0f, c->stream);
+            break;
+        }
+        case SFB_PROBE_MFMA_F32:
+        case SFB_PROBE_MFMA_BF16: {
+            if (param != 1 && param != 2) return SFB_EINVAL;
+            Timed t(c, 3);
+            e = launch_probe_mfma(kind == SFB_PROBE_MFMA_BF16, param, SFB_PROBE_MFMA_ITERS, (float*)c->ws, c->stream);
+            break;
+        }
+        default: return SFB_EINVAL;
+    }
+    if (e != hipSuccess) return hip_fail(c, e);
+    return SFB_OK;
+}
+
 sfb_status sfb_enable_timing(sfb_ctx* c, int enable) {
     if (!c) return SFB_EINVAL;
     c->timing = enable != 0;

@@ -108,6 +108,12 @@ hipError_t launch_csr_scores(const DensifyArgs& a, const float* W, int64_t ldw, 
 // dst[0 .. bytes) = src[0 .. bytes); both 16-byte aligned, bytes a multiple of 16.
 hipError_t launch_stream_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
 
+// Measurement aids (sfb_probe.hip): the bare memory traffic / matrix-core work of a kernel, in its access shape.
+hipError_t launch_probe_w_stream(const float* W, int64_t ldw, int J, int D, int k_slice, int dup, float* sink,
+                                 hipStream_t s);
+hipError_t launch_probe_w_rmw(float* W, int64_t ldw, int J, int D, float add, hipStream_t s);
+hipError_t launch_probe_mfma(bool bf16, int waves_per_simd, int iters, float* sink, hipStream_t s);
+
 // Proximal step on W (Section 2.1).  kind: 0 identity, 1 squared l2 (param = lam), 2 l1
 // (param = lam), 3 projection of every column onto the l2 ball of radius param (needs
 // prox_workspace(J, D) bytes of 16-byte aligned device memory).

@@ -1,0 +1,140 @@
+// Measurement aids, not part of the method: kernels that do nothing but the memory traffic or
+// the matrix-core work of one of the path's kernels, in that kernel's own access shape.  Their
+// durations are the floors the real kernels are compared with: what the part delivers for that
+// shape when nothing else competes for the compute unit.
+//   probe_w_stream   reads W once the way the bf16 score pass does: a workgroup walks a block of
+//                    256 rows along its slice of D, 128 bytes of every row per step, several steps
+//                    in flight; `dup` workgroups read the same block (the score pass has one per
+//                    sample block, so dup = 2 at N = 512)
+//   probe_w_rmw      W += c in the tile and lane mapping of the bf16 reconstruction's epilogue:
+//                    256 x 128 tiles, 2 x 2 wavefronts, the MFMA accumulator layout (lane = column,
+//                    16 rows per 32 x 32 block), four blocks of loads in flight
+//   probe_mfma       a register-resident loop of matrix-core instructions (no memory traffic):
+//                    the rate the matrix cores sustain at the clock the part holds under that load
+#include "sfb_device.h"
+#include "sfb_kernels.h"
+
+namespace sfb {
+
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+
+__global__ __launch_bounds__(512) void probe_w_stream_kernel(const float* __restrict__ W, int64_t ldw, int J, int D,
+                                                             int k_slice, int n_nb, int dup, float* __restrict__ sink) {
+    // 512 lanes x 2 pieces of 32 bytes = 256 rows x 128 bytes per step
+    const int bid = blockIdx.x / dup, nb = bid % n_nb, ks = bid / n_nb;
+    const int tid = threadIdx.x;
+    const int k0 = ks * k_slice, k1 = min(D, k0 + k_slice);
+    const int steps = (k1 - k0) / 32;                       // whole 32-float steps only (host: D % 32 == 0)
+    if (steps <= 0) return;
+    const float* p[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int s = tid + i * 512, r = s / 4, c = s % 4;
+        p[i] = W + (int64_t)min(nb * 256 + r, J - 1) * ldw + k0 + c * 8;
+    }
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    f32x4 r0[4], r1[4], r2[4];
+    auto fetch = [&](f32x4* r, int st) {
+        const int o = min(st, steps - 1) * 32;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            r[2 * i] = *reinterpret_cast<const f32x4*>(p[i] + o);
+            r[2 * i + 1] = *reinterpret_cast<const f32x4*>(p[i] + o + 4);
+        }
+    };
+    auto use = [&](const f32x4* r) { acc += r[0] + r[1] + r[2] + r[3]; };
+    fetch(r0, 0); fetch(r1, 1); fetch(r2, 2);
+    int st = 0;
+    for (; st + 3 <= steps; st += 3) {
+        use(r0); fetch(r0, st + 3); __builtin_amdgcn_sched_barrier(0);
+        use(r1); fetch(r1, st + 4); __builtin_amdgcn_sched_barrier(0);
+        use(r2); fetch(r2, st + 5); __builtin_amdgcn_sched_barrier(0);
+    }
+    use(r0); use(r1); use(r2);
+    // never true for finite data; keeps the loads alive
+    if (acc[0] + acc[1] + acc[2] + acc[3] == 12345.678f) sink[blockIdx.x % 64] = acc[0];
+}
+
+__global__ __launch_bounds__(256, 2) void probe_w_rmw_kernel(float* __restrict__ W, int64_t ldw, int J, int D, int n_nb,
+                                                             float add) {
+    constexpr int BM = 256, BN = 128, WM = BM / 2, WN = BN / 2, MT = WM / 32, NT = WN / 32, EG = 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int mb = blockIdx.x / n_nb, nb = blockIdx.x % n_nb;
+    const int m0 = mb * BM, n0 = nb * BN;
+#pragma unroll
+    for (int g = 0; g < MT * NT; g += EG) {
+        float w[EG][16];
+#pragma unroll
+        for (int b = 0; b < EG; ++b) {
+            const int i = (g + b) / NT, j = (g + b) % NT;
+            const int cc = min(n0 + wn * WN + j * 32 + l32, D - 1);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                w[b][e] = W[(int64_t)min(row, J - 1) * ldw + cc];
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < EG; ++b) {
+            const int i = (g + b) / NT, j = (g + b) % NT;
+            const int col = n0 + wn * WN + j * 32 + l32;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = m0 + wm * WM + i * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+                if (row < J && col < D) W[(int64_t)row * ldw + col] = w[b][e] + add;
+            }
+        }
+    }
+}
+
+// 16 matrix-core instructions per iteration on four independent accumulators
+template <bool BF16>
+__global__ __launch_bounds__(512) void probe_mfma_kernel(float* __restrict__ sink, int iters, float a0, float b0) {
+    f32x16 acc[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
+    const float a = a0 + threadIdx.x * 1e-6f, b = b0;
+    probe_bf16x8 ab, bb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { ab[e] = (__bf16)a; bb[e] = (__bf16)b; }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int n = 0; n < 4; ++n) {
+                if (BF16) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, bb, acc[n], 0, 0, 0);
+                else acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[n], 0, 0, 0);
+            }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[n][e];
+    sink[(blockIdx.x * blockDim.x + threadIdx.x) % 64] = s;       // 64 floats of sink: last writer wins, value unused
+}
+
+hipError_t launch_probe_w_stream(const float* W, int64_t ldw, int J, int D, int k_slice, int dup, float* sink,
+                                 hipStream_t s) {
+    const int n_nb = (J + 255) / 256, n_ks = (D + k_slice - 1) / k_slice;
+    SFB_LAUNCH(probe_w_stream_kernel, dim3(n_nb * n_ks * dup), dim3(512), 0, s, W, ldw, J, D, k_slice, n_nb, dup, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_w_rmw(float* W, int64_t ldw, int J, int D, float add, hipStream_t s) {
+    const int n_mb = (J + 255) / 256, n_nb = (D + 127) / 128;
+    SFB_LAUNCH(probe_w_rmw_kernel, dim3(n_mb * n_nb), dim3(256), 0, s, W, ldw, J, D, n_nb, add);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_mfma(bool bf16, int waves_per_simd, int iters, float* sink, hipStream_t s) {
+    const dim3 grid(256), block(256 * waves_per_simd);            // one workgroup per compute unit
+    if (bf16) SFB_LAUNCH(probe_mfma_kernel<true>, grid, block, 0, s, sink, iters, 1.0f, 1e-3f);
+    else SFB_LAUNCH(probe_mfma_kernel<false>, grid, block, 0, s, sink, iters, 1.0f, 1e-3f);
+    return hipGetLastError();
+}
+
+}  // namespace sfb
