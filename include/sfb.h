@@ -69,7 +69,9 @@ typedef enum {
     SFB_EDTYPE = -3,       /* unknown dtype                                                  */
     SFB_EWORKSPACE = -5,   /* workspace missing or smaller than sfb_workspace_bytes          */
     SFB_EUNSUPPORTED = -6, /* (model, dtype) combination or size the kernels do not cover    */
-    SFB_EHIP = -7          /* a HIP call failed; see sfb_last_hip_error                      */
+    SFB_EHIP = -7,         /* a HIP call failed; see sfb_last_hip_error                      */
+    SFB_ESCRATCH = -8      /* sfb_step_noalloc: the context needs more scratch than
+                              SFB_NOALLOC_SCRATCH_BYTES                                      */
 } sfb_status;
 
 /*
@@ -161,6 +163,26 @@ SFB_API sfb_status sfb_reconstruct_apply_worker(sfb_ctx *ctx, float *W, int64_t 
 SFB_API sfb_status sfb_step(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_batch *batch, const int32_t *y,
                     float *U, int64_t ldu, void *V, int64_t ldv, float *loss, float eta,
                     const uint8_t *active);
+
+/*
+ * sfb_step for callers that cannot allocate or register device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * same results as sfb_step, bit for bit, but the scratch the kernels need (split-K partial scores)
+ * is a fixed array of SFB_NOALLOC_SCRATCH_BYTES of device memory inside the library, one copy per
+ * GPU, instead of the workspace registered with sfb_set_workspace (which this call neither needs
+ * nor touches).  The call allocates and frees nothing, on the host or on the device.
+ *   - SFB_ESCRATCH (nothing launched) if sfb_workspace_bytes(ctx) exceeds SFB_NOALLOC_SCRATCH_BYTES;
+ *     of the benchmark shapes every one but the 10000 x 21504 bf16 one fits.
+ *   - The context must have been created with the GPU current that the call runs on (sfb_create
+ *     resolves the array's address for that GPU).
+ *   - All calls on one GPU share that GPU's array, from whatever context or stream: calls that may
+ *     overlap in time race on it.  Serialise them (one stream, or events between streams).
+ *     Nothing needs clearing between calls: a step writes every scratch byte before it reads it.
+ */
+#define SFB_NOALLOC_SCRATCH_BYTES ((size_t)16 << 20)
+SFB_API sfb_status sfb_step_noalloc(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_batch *batch,
+                                    const int32_t *y, float *U, int64_t ldu, void *V, int64_t ldv,
+                                    float *loss, float eta, const uint8_t *active);
 
 /*
  * SFB driven by stochastic dual coordinate ascent (Section 2.1, "Stochastic DCA") for the

@@ -53,6 +53,7 @@ def _load():
         "sfb_compute_factors_worker": (C.c_int, [vp, vp, i64, pb, vp, i32, vp, i64, vp, i64, vp]),
         "sfb_reconstruct_apply": (C.c_int, [vp, vp, i64, vp, i64, vp, i64, f32, f32, vp]),
         "sfb_step": (C.c_int, [vp, vp, i64, pb, vp, vp, i64, vp, i64, vp, f32, vp]),
+        "sfb_step_noalloc": (C.c_int, [vp, vp, i64, pb, vp, vp, i64, vp, i64, vp, f32, vp]),
         "sfb_default_scale": (C.c_int, [vp, C.POINTER(f32)]),
         "sfb_sync": (C.c_int, [vp]),
         "sfb_strerror": (C.c_char_p, [C.c_int]),
@@ -228,6 +229,16 @@ class Sfb:
         self._check(lib.sfb_step(self._ctx, W.data_ptr(), W.stride(0), C.byref(b), y.data_ptr(), U.data_ptr(),
                                  U.stride(0), V.data_ptr(), V.stride(0), _ptr(loss), float(eta), ptr),
                     "sfb_step")
+
+    def step_noalloc(self, W, batch, y, U, V, eta, loss=None, active=None):
+        """sfb_step on the library's own fixed scratch array (no workspace, nothing allocated)."""
+        if active is not None and len(active) != self.P:
+            raise ValueError("active mask must have P entries")
+        b = batch.c_struct()
+        keep, ptr = self._mask(active)
+        self._check(lib.sfb_step_noalloc(self._ctx, W.data_ptr(), W.stride(0), C.byref(b), y.data_ptr(),
+                                         U.data_ptr(), U.stride(0), V.data_ptr(), V.stride(0), _ptr(loss),
+                                         float(eta), ptr), "sfb_step_noalloc")
 
     # -- proximal step ---------------------------------------------------------
     PROX_KINDS = {"none": 0, "l2sq": 1, "l1": 2, "column_ball": 3}

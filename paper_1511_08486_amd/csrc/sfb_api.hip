@@ -17,6 +17,34 @@ using namespace sfb;
 namespace {
 constexpr int kFamilies = 5;  // 0 scores, 1 factor u, 2 reconstruct-apply, 3 sparse helpers, 4 proximal step
 struct EventPair { hipEvent_t a, b; };
+
+// Scratch of the entry point that allocates nothing (sfb_step_noalloc): device memory that belongs
+// to the library's code object, one copy per GPU the library is loaded on, held until the process
+// ends.  It plays the role of the registered workspace (split-K partial scores, packed bf16
+// factors), every byte of which a step writes before reading it, so nothing has to be cleared
+// between calls.  In host code the array's NAME is only a handle for hipGetSymbolAddress; kernels
+// are given the device address kept in static_scratch_ptr.
+constexpr size_t kStaticScratchBytes = SFB_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> static_scratch_ptr[kMaxDevices];     // zero-initialised: not resolved yet
+
+// Device address of `scratch` on the current device, resolved once per device.
+hipError_t resolve_static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* p = static_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        static_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread resolves the same address
+    }
+    *out = p;
+    return hipSuccess;
+}
 }  // namespace
 
 namespace sfb {
@@ -295,6 +323,14 @@ sfb_status sfb_create(sfb_ctx** out, sfb_model m, int64_t J, int64_t D, int32_t 
     c->split_recon = false;
     c->recon = plan_reconstruct(J, D, (int64_t)P * B);
     c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->timing = false; c->sparse_forward = true;
+    // Set-up for sfb_step_noalloc on the device that is current now: resolve the address of the
+    // library's scratch array, so that the entry point itself only reads it.  On a machine without a
+    // GPU this fails; the context is still good for everything that can be checked on the host, and
+    // the entry point tries again (and reports SFB_EHIP if it still cannot).
+    {
+        void* unused = nullptr;
+        if (resolve_static_scratch(&unused) != hipSuccess) (void)hipGetLastError();
+    }
     *out = c;
     return SFB_OK;
 }
@@ -375,6 +411,30 @@ sfb_status sfb_step(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, c
     s = factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss);
     if (s != SFB_OK) return s;
     return recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active);
+}
+
+sfb_status sfb_step_noalloc(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, const int32_t* y, float* U,
+                            int64_t ldu, void* V, int64_t ldv, float* loss, float eta, const uint8_t* active) {
+    sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
+    if (s != SFB_OK) return s;
+    s = check_batch(c, batch, y);
+    if (s != SFB_OK) return s;
+    float scale;
+    (void)sfb_default_scale(c, &scale);
+    s = check_recon(c, eta, scale, active);
+    if (s != SFB_OK) return s;
+    if (workspace_need(c) > kStaticScratchBytes) return SFB_ESCRATCH;
+    void* ptr = nullptr;
+    hipError_t e = resolve_static_scratch(&ptr);     // a table read after sfb_create on this device
+    if (e != hipSuccess) return hip_fail(c, e);
+    // the kernels take the scratch address where they take the registered workspace in sfb_step
+    void* const ws = c->ws;
+    const size_t ws_bytes = c->ws_bytes;
+    c->ws = ptr; c->ws_bytes = kStaticScratchBytes;
+    s = factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss);
+    if (s == SFB_OK) s = recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active);
+    c->ws = ws; c->ws_bytes = ws_bytes;
+    return s;
 }
 
 sfb_status sfb_sdca_compute_factors(sfb_ctx* c, const float* W, int64_t ldw, const sfb_batch* batch,
@@ -500,6 +560,7 @@ const char* sfb_strerror(sfb_status s) {
         case SFB_EWORKSPACE: return "workspace missing or too small";
         case SFB_EUNSUPPORTED: return "unsupported model/dtype combination or size";
         case SFB_EHIP: return "HIP runtime error";
+        case SFB_ESCRATCH: return "the context needs more scratch than the library's fixed array holds (use sfb_step with a registered workspace)";
     }
     return "unknown status";
 }

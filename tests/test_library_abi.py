@@ -259,3 +259,23 @@ def test_measurement_aids_validate_their_arguments(lib):
     assert lib.sfb_last_hip_error(ctx) == 0
     lib.sfb_destroy(ctx)
     lib.sfb_destroy(None)                                                     # harmless
+
+
+def test_noalloc_step_rejects_what_its_fixed_scratch_cannot_hold(lib):
+    """Fake non-null pointers are safe here: the size check fails first, nothing is launched."""
+    import paper_1511_08486_amd as sfb
+    assert "sfb_step_noalloc" in declared_symbols()
+    fake = C.c_void_p(0x1000)
+    b = sfb.binding.sfb_batch()
+    ctx = C.c_void_p()
+    # 10000 x 21504 bf16: 61 MB of partial scores + 32 MB of packed factors > the 16 MiB array
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 10000, 21504, 16, 32, sfb.SFB_BF16, None) == 0
+    need = C.c_size_t()
+    assert lib.sfb_workspace_bytes(ctx, C.byref(need)) == 0 and need.value > (16 << 20)
+    b.a, b.lda = 0x1000, 21504
+    assert lib.sfb_step_noalloc(ctx, fake, 21504, C.byref(b), fake, fake, 10000, fake, 21504, None, 0.1, None) == -8
+    assert b"scratch" in lib.sfb_strerror(-8)
+    # the other argument checks come first, as in sfb_step
+    assert lib.sfb_step_noalloc(ctx, None, 21504, C.byref(b), fake, fake, 10000, fake, 21504, None, 0.1, None) == -1
+    assert lib.sfb_step_noalloc(ctx, fake, 21503, C.byref(b), fake, fake, 10000, fake, 21504, None, 0.1, None) == -2
+    lib.sfb_destroy(ctx)
