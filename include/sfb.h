@@ -165,6 +165,28 @@ SFB_API sfb_status sfb_step(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_batch
                     const uint8_t *active);
 
 /*
+ * The same iterations regrouped so that W crosses memory once per iteration instead of three
+ * times: apply the pending factors (U, V hold those of iteration t: the update of Section 2.1 with the
+ * reconstruction of Section 3, scale 1/B), then compute the factors of iteration t+1 at the W just
+ * produced (Section 2.1: every iteration differentiates at the current W), leaving them in U, V
+ * (and loss) as the new pending factors.  A run is
+ *     sfb_compute_factors(W, batch_0) ; sfb_step_pipelined(W, batch_1) ; ... ; sfb_step_pipelined(W, batch_T-1) ;
+ *     sfb_reconstruct_apply(W, U, V, eta, 1/B)
+ * and gives what T calls of sfb_step give.  For bf16 contexts whose shape the fused kernel covers
+ * (P*B in {128, 256, 512}, D a multiple of 32, J*ldw < 2^31, 16-byte aligned operands) the update and
+ * the next scores run in ONE kernel that reads and writes every tile of W once; otherwise the call runs
+ * sfb_reconstruct_apply and sfb_compute_factors one after the other (same results as sfb_step).
+ * `active` masks the workers of the PENDING factors.  Needs the registered workspace (query
+ * sfb_workspace_bytes).  Errors as sfb_step; nothing is launched if an argument is refused.
+ * sfb_pipeline_info: whether the fused kernel is what the context would run (0 / 1), its grid and
+ * its number of column slices (0 when not fused); any pointer may be NULL.
+ */
+SFB_API sfb_status sfb_step_pipelined(sfb_ctx *ctx, float *W, int64_t ldw, float *U, int64_t ldu, void *V,
+                                      int64_t ldv, const sfb_batch *next_batch, const int32_t *next_y,
+                                      float *loss, float eta, const uint8_t *active);
+SFB_API sfb_status sfb_pipeline_info(const sfb_ctx *ctx, int32_t *fused, int32_t *grid, int32_t *slices);
+
+/*
  * sfb_step for callers that cannot allocate or register device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
  * same results as sfb_step, bit for bit, but the scratch the kernels need (split-K partial scores)
@@ -297,7 +319,7 @@ SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32
  * exactly into three bf16 terms and every product taken as its six leading term products (error
  * at the level of one fp32 rounding; full batch and 16-byte aligned rows only, else ignored);
  * bit 3 = the same for the fp32 reconstruction (J, D multiples of 4, N a multiple of 32, no dead
- * workers, else ignored); < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.
+ * workers, else ignored); bit 4 = sfb_step_pipelined always runs its two separate passes; < 0 = keep.  A value <= 0 (variant < 0) keeps the current choice.
  * The workspace requirement may grow: query sfb_workspace_bytes again.  SFB_EINVAL for a value outside the table. */
 SFB_API sfb_status sfb_set_plan(sfb_ctx *ctx, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_split_k,
                                 int32_t recon_variant, int32_t fwd_dma);

@@ -53,6 +53,8 @@ def _load():
         "sfb_compute_factors_worker": (C.c_int, [vp, vp, i64, pb, vp, i32, vp, i64, vp, i64, vp]),
         "sfb_reconstruct_apply": (C.c_int, [vp, vp, i64, vp, i64, vp, i64, f32, f32, vp]),
         "sfb_step": (C.c_int, [vp, vp, i64, pb, vp, vp, i64, vp, i64, vp, f32, vp]),
+        "sfb_step_pipelined": (C.c_int, [vp, vp, i64, vp, i64, vp, i64, pb, vp, vp, f32, vp]),
+        "sfb_pipeline_info": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
         "sfb_step_noalloc": (C.c_int, [vp, vp, i64, pb, vp, vp, i64, vp, i64, vp, f32, vp]),
         "sfb_default_scale": (C.c_int, [vp, C.POINTER(f32)]),
         "sfb_sync": (C.c_int, [vp]),
@@ -229,6 +231,25 @@ class Sfb:
         self._check(lib.sfb_step(self._ctx, W.data_ptr(), W.stride(0), C.byref(b), y.data_ptr(), U.data_ptr(),
                                  U.stride(0), V.data_ptr(), V.stride(0), _ptr(loss), float(eta), ptr),
                     "sfb_step")
+
+    def update_and_next_factors(self, W, U, V, next_batch, next_y, eta, loss=None, active=None):
+        """sfb_step_pipelined: apply the pending factors in U, V to W, then leave the next batch's factors there."""
+        if active is not None and len(active) != self.P:
+            raise ValueError("active mask must have P entries")
+        b = next_batch.c_struct()
+        keep, ptr = self._mask(active)
+        self._check(lib.sfb_step_pipelined(self._ctx, W.data_ptr(), W.stride(0), U.data_ptr(), U.stride(0),
+                                           V.data_ptr(), V.stride(0), C.byref(b), next_y.data_ptr(), _ptr(loss),
+                                           float(eta), ptr), "sfb_step_pipelined")
+
+    def pipeline_info(self):
+        a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+        self._check(lib.sfb_pipeline_info(self._ctx, C.byref(a), C.byref(b), C.byref(c)), "sfb_pipeline_info")
+        return {"fused": bool(a.value), "grid": b.value, "slices": c.value}
+
+    def pipeline_ok(self):
+        """True if sfb_step_pipelined would run its one-pass kernel for this context's shape."""
+        return self.pipeline_info()["fused"]
 
     def step_noalloc(self, W, batch, y, U, V, eta, loss=None, active=None):
         """sfb_step on the library's own fixed scratch array (no workspace, nothing allocated)."""

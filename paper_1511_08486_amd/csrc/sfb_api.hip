@@ -66,6 +66,8 @@ struct sfb_ctx {
     bool split_scores;             // use it where the shape allows
     bool split_recon;              // reconstruction with split-bf16 products where the shape allows
     ReconPlan recon;
+    FusedPlan fused;               // update fused with the next scores (bf16 contexts whose shape it covers)
+    bool fused_ok, use_fused;
     void* ws;
     size_t ws_bytes;
     int last_hip;
@@ -92,6 +94,10 @@ size_t scores_need(const sfb_ctx* c) {
         const size_t sp = (size_t)c->fwd_split.split_k * (size_t)c->P * c->B * ldz * sizeof(float);
         if (sp > need) need = sp;
     }
+    if (c->fused_ok) {
+        const size_t fu = (size_t)c->fused.slices * (size_t)c->P * c->B * ldz * sizeof(float);
+        if (fu > need) need = fu;
+    }
     return (need + 255) / 256 * 256;
 }
 
@@ -99,6 +105,7 @@ size_t scores_need(const sfb_ctx* c) {
 size_t workspace_need(const sfb_ctx* c) {
     size_t need = scores_need(c);
     if (c->dtype == SFB_BF16) need += bf16_recon_workspace(c->J, c->D, (int64_t)c->P * c->B);
+    if (c->fused_ok) need += fused_extra_workspace(c->D, (int64_t)c->P * c->B);   // staged next features, last
     // the column projection of the proximal step reuses the front of the buffer between steps
     const size_t prox = prox_workspace(c->J, c->D);
     return need > prox ? need : prox;
@@ -169,6 +176,23 @@ sfb_status check_batch(const sfb_ctx* c, const sfb_batch* b, const int32_t* y) {
     return SFB_OK;
 }
 
+// Factor u (and the loss) of `n_rows` samples from the `split_k` partial scores at the front of the workspace.
+sfb_status factor_rows(sfb_ctx* c, int split_k, int64_t zstride, const int32_t* y, int64_t row0, int n_rows, float* U,
+                       int64_t ldu, float* loss, const sfb_sdca* sdca) {
+    FactorArgs g{};
+    g.zp = (const float*)c->ws; g.ldz = round_up4(c->J); g.zstride = zstride; g.split_k = split_k;
+    g.y = y; g.u = U + row0 * ldu; g.ldu = ldu; g.loss = loss ? loss + row0 : nullptr;
+    g.n_rows = n_rows; g.J = (int)c->J; g.model = (Model)c->model;
+    if (sdca) {
+        const bool vec = ((uintptr_t)sdca->dual % 16) == 0 && (sdca->ld_dual % 4) == 0;
+        g.sdca = SdcaDev{sdca->sample, sdca->dual, sdca->ld_dual, sdca->conj, sdca->s, vec};
+    }
+    Timed t(c, 1);
+    hipError_t e = launch_factor(g, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e);
+    return SFB_OK;
+}
+
 // Factors of `n_rows` samples whose outputs start at row `row0` of U, V, loss.
 sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t ldw, const sfb_batch* b,
                         const int32_t* y, int64_t row0, int n_rows, float* U, int64_t ldu, void* V,
@@ -219,20 +243,7 @@ sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t
                                      : launch_forward(f, used, c->stream);
         if (e != hipSuccess) return hip_fail(c, e);
     }
-    FactorArgs g{};
-    g.zp = (const float*)c->ws; g.ldz = ldz; g.zstride = f.zstride; g.split_k = sparse_scores ? 1 : used.split_k;
-    g.y = y; g.u = U + row0 * ldu; g.ldu = ldu; g.loss = loss ? loss + row0 : nullptr;
-    g.n_rows = n_rows; g.J = (int)c->J; g.model = (Model)c->model;
-    if (sdca) {
-        const bool vec = ((uintptr_t)sdca->dual % 16) == 0 && (sdca->ld_dual % 4) == 0;
-        g.sdca = SdcaDev{sdca->sample, sdca->dual, sdca->ld_dual, sdca->conj, sdca->s, vec};
-    }
-    {
-        Timed t(c, 1);
-        hipError_t e = launch_factor(g, c->stream);
-        if (e != hipSuccess) return hip_fail(c, e);
-    }
-    return SFB_OK;
+    return factor_rows(c, sparse_scores ? 1 : used.split_k, f.zstride, y, row0, n_rows, U, ldu, loss, sdca);
 }
 
 sfb_status check_sdca(const sfb_ctx* c, const sfb_sdca* d) {
@@ -322,6 +333,9 @@ sfb_status sfb_create(sfb_ctx** out, sfb_model m, int64_t J, int64_t D, int32_t 
     c->split_scores = false;
     c->split_recon = false;
     c->recon = plan_reconstruct(J, D, (int64_t)P * B);
+    c->fused_ok = input_dtype == SFB_BF16 && m == SFB_MLR && fused_shape_ok(J, D, (int64_t)P * B);
+    c->use_fused = true;
+    c->fused = c->fused_ok ? plan_fused(J, D, (int64_t)P * B) : FusedPlan{};
     c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->timing = false; c->sparse_forward = true;
     // Set-up for sfb_step_noalloc on the device that is current now: resolve the address of the
     // library's scratch array, so that the entry point itself only reads it.  On a machine without a
@@ -411,6 +425,61 @@ sfb_status sfb_step(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, c
     s = factors_rows(c, c->fwd_all, W, ldw, batch, y, 0, c->P * c->B, U, ldu, V, ldv, loss);
     if (s != SFB_OK) return s;
     return recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active);
+}
+
+sfb_status sfb_step_pipelined(sfb_ctx* c, float* W, int64_t ldw, float* U, int64_t ldu, void* V, int64_t ldv,
+                              const sfb_batch* next_batch, const int32_t* next_y, float* loss, float eta,
+                              const uint8_t* active) {
+    sfb_status s = check_common(c, W, ldw, U, ldu, V, ldv);
+    if (s != SFB_OK) return s;
+    s = check_batch(c, next_batch, next_y);
+    if (s != SFB_OK) return s;
+    float scale;
+    (void)sfb_default_scale(c, &scale);
+    s = check_recon(c, eta, scale, active);
+    if (s != SFB_OK) return s;
+    if (c->ws == nullptr || c->ws_bytes < workspace_need(c)) return SFB_EWORKSPACE;
+    const int N = c->P * c->B;
+    if (c->fused_ok && c->use_fused) {
+        FusedArgs f{};
+        f.w = W; f.ldw = ldw; f.u = U; f.ldu = ldu; f.v = V; f.ldv = ldv;
+        f.a_next = next_batch->a; f.lda = next_batch->lda;
+        f.zp = (float*)c->ws; f.ldz = round_up4(c->J); f.zstride = (int64_t)N * f.ldz;
+        f.J = (int)c->J; f.D = (int)c->D; f.N = N; f.B = c->B;
+        f.alpha = -eta * scale;
+        f.live_mask = ~0ull; f.use_mask = false;
+        if (active) {
+            uint64_t m = 0;
+            bool all = true;
+            for (int p = 0; p < c->P; ++p) {
+                if (active[p]) m |= (1ull << p); else all = false;
+            }
+            f.live_mask = m; f.use_mask = !all;
+        }
+        if (fused_call_ok(f)) {
+            char* ws_factors = (char*)c->ws + scores_need(c);
+            char* ws_next = ws_factors + bf16_recon_workspace(c->J, c->D, N);
+            {
+                Timed t(c, 2);
+                hipError_t e = launch_fused(f, c->fused, ws_factors, ws_next, c->stream);
+                if (e != hipSuccess) return hip_fail(c, e);
+            }
+            return factor_rows(c, c->fused.slices, f.zstride, next_y, 0, N, U, ldu, loss, nullptr);
+        }
+    }
+    // the same two steps as separate passes over W
+    s = recon_launch(c, W, ldw, U, ldu, V, ldv, eta, scale, active);
+    if (s != SFB_OK) return s;
+    return factors_rows(c, c->fwd_all, W, ldw, next_batch, next_y, 0, N, U, ldu, V, ldv, loss);
+}
+
+sfb_status sfb_pipeline_info(const sfb_ctx* c, int32_t* fused, int32_t* grid, int32_t* slices) {
+    if (!c) return SFB_EINVAL;
+    const bool on = c->fused_ok && c->use_fused;
+    if (fused) *fused = on ? 1 : 0;
+    if (grid) *grid = on ? c->fused.grid : 0;
+    if (slices) *slices = on ? c->fused.slices : 0;
+    return SFB_OK;
 }
 
 sfb_status sfb_step_noalloc(sfb_ctx* c, float* W, int64_t ldw, const sfb_batch* batch, const int32_t* y, float* U,
@@ -590,6 +659,7 @@ sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_
     if (fwd_dma >= 0) c->sparse_forward = (fwd_dma & 2) == 0;   // bit 1 set: dense scores for CSR input
     if (fwd_dma >= 0) c->split_scores = (fwd_dma & 4) != 0;     // bit 2 set: fp32 scores as split-bf16 products
     if (fwd_dma >= 0) c->split_recon = (fwd_dma & 8) != 0;      // bit 3 set: the reconstruction likewise
+    if (fwd_dma >= 0) c->use_fused = (fwd_dma & 16) == 0;       // bit 4 set: sfb_step_pipelined runs two separate passes
     finish_forward_plan(&p, (int64_t)c->P * c->B, c->J, c->D);
     c->fwd_all = p;
     if (recon_variant >= 0) c->recon = plan_reconstruct_variant(c->J, c->D, recon_variant);

@@ -166,4 +166,25 @@ int bf16_recon_grid(int64_t J, int64_t D);                     // workgroups of 
 // ws: bf16_recon_workspace bytes, 256-byte aligned.  Two launches: transpose/pack, then W += C.
 hipError_t launch_reconstruct_bf16(const ReconArgs& a, void* ws, hipStream_t s);
 
+// Update of iteration t fused with the scores of iteration t+1, one pass over W (sfb_fused.hip; bf16 contexts).
+struct FusedPlan {
+    int n_bands, slices, k_slice, grid;
+};
+struct FusedArgs {
+    float* w; int64_t ldw;             // [J][ldw] read-modify-write
+    const float* u; int64_t ldu;       // [N][ldu] factors of iteration t
+    void* v; int64_t ldv;              // [N][ldv] bf16: v_t on entry, the next batch's features on return
+    const void* a_next; int64_t lda;   // [N][lda] bf16 features of iteration t+1
+    float* zp; int64_t ldz, zstride;   // [slices][N][ldz] partial scores of iteration t+1 out
+    int J, D, N, B;
+    float alpha;
+    uint64_t live_mask;
+    bool use_mask;
+};
+bool fused_shape_ok(int64_t J, int64_t D, int64_t N);
+FusedPlan plan_fused(int64_t J, int64_t D, int64_t N);
+size_t fused_extra_workspace(int64_t D, int64_t N);
+bool fused_call_ok(const FusedArgs& a);   // alignment and size of this call's operands
+hipError_t launch_fused(const FusedArgs& a, const FusedPlan& p, void* ws_factors, void* ws_next, hipStream_t s);
+
 }  // namespace sfb

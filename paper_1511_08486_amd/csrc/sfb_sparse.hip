@@ -8,33 +8,55 @@ namespace sfb {
 
 constexpr int kDensifyThreads = 256;
 
-// One workgroup per sample: zero the row with wide stores, then add the stored entries
-// into it.  The barrier orders the two phases inside the workgroup, and no other
-// workgroup touches this row.  Entries are ADDED (hardware fp32 atomic), so a column that
-// appears more than once in a row contributes the sum of its values, exactly as it does in
-// the scores computed from the stored entries; a column that appears once lands bit for bit
-// (0 + v = v).  With three or more repeats the order of the additions is not fixed.
+// One workgroup per sample.  Entries are ADDED into a zeroed row, so a column that appears more than
+// once in a row contributes the sum of its values, exactly as it does in the scores computed from the
+// stored entries; a column that appears once lands bit for bit (0 + v = v).  With three or more
+// repeats the order of the additions is not fixed.
+//   IN_LDS: the row is built in LDS (zero, barrier, LDS atomic adds, barrier) and written out once
+//           with wide coalesced stores: one pass over the row in memory, no atomics on memory.
+//   else:   rows longer than the LDS holds are zeroed in memory with wide stores and the entries
+//           added with fp32 atomics on memory (the barrier orders the two phases inside the
+//           workgroup, and no other workgroup touches this row).
+template <bool IN_LDS>
 __global__ __launch_bounds__(kDensifyThreads) void csr_densify_kernel(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ col, const float* __restrict__ val,
     float* __restrict__ V, int64_t ldv, int D, int64_t nnz, bool vec_v) {
+    extern __shared__ __attribute__((aligned(16))) float dense_row[];   // [round_up4(D)] when IN_LDS
     const int row = blockIdx.x;
     float* out = V + (int64_t)row * ldv;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 4 * threadIdx.x; c < D; c += 4 * kDensifyThreads) store4(out, c, D, vec_v, zero);
+    for (int c = 4 * threadIdx.x; c < D; c += 4 * kDensifyThreads) {
+        if (IN_LDS) *reinterpret_cast<f32x4*>(&dense_row[c]) = zero;
+        else store4(out, c, D, vec_v, zero);
+    }
     __syncthreads();
     // a row pointer outside [0, nnz] is a caller error; clamp so that no access leaves the arrays
     const int64_t beg = max(0, rowptr[row]);
     const int64_t end = min((int64_t)rowptr[row + 1], nnz);
     for (int64_t n = beg + threadIdx.x; n < end; n += kDensifyThreads) {
         const int c = col[n];
-        if (c >= 0 && c < D) unsafeAtomicAdd(out + c, val[n]);
+        if (c >= 0 && c < D) {
+            if (IN_LDS) atomicAdd(&dense_row[c], val[n]);
+            else unsafeAtomicAdd(out + c, val[n]);
+        }
+    }
+    if (IN_LDS) {
+        __syncthreads();
+        for (int c = 4 * threadIdx.x; c < D; c += 4 * kDensifyThreads)
+            store4(out, c, D, vec_v, *reinterpret_cast<const f32x4*>(&dense_row[c]));
     }
 }
 
 hipError_t launch_csr_densify(const DensifyArgs& a, hipStream_t s) {
     const bool vec_v = ((uintptr_t)a.v % 16) == 0 && (a.ldv % 4) == 0;
-    SFB_LAUNCH(csr_densify_kernel, dim3(a.n_rows), dim3(kDensifyThreads), 0, s, a.rowptr, a.col,
-                       a.val, a.v, a.ldv, a.D, a.nnz, vec_v);
+    const size_t lds_bytes = ((size_t)a.D + 3) / 4 * 16;
+    if (lds_bytes <= 64 * 1024) {
+        SFB_LAUNCH(csr_densify_kernel<true>, dim3(a.n_rows), dim3(kDensifyThreads), lds_bytes, s, a.rowptr, a.col,
+                   a.val, a.v, a.ldv, a.D, a.nnz, vec_v);
+    } else {
+        SFB_LAUNCH(csr_densify_kernel<false>, dim3(a.n_rows), dim3(kDensifyThreads), 0, s, a.rowptr, a.col,
+                   a.val, a.v, a.ldv, a.D, a.nnz, vec_v);
+    }
     return hipGetLastError();
 }
 

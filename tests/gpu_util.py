@@ -138,3 +138,62 @@ def run_chain(wl, steps, tol, check_every=1, dml_guard=1e-4, pad=0, plan=None, p
             progress(f"{wl.name}: step {t + 1}/{steps}" + (f" checked, worst error/allowance so far {worst}" if checked else ""))
     ctx.close()
     return worst
+
+
+def run_chain_pipelined(wl, steps, tol, check_every=1, plan=None, progress=None, active=None):
+    """The same `steps` iterations as run_chain, regrouped the way sfb_step_pipelined runs them: factors of
+    batch 0, then steps - 1 calls that apply the pending factors and form the next batch's, then the last
+    update.  After call t the GPU's W must be the oracle's W after t updates and U, V, loss the oracle's
+    factors of batch t at that W; the update a call applies is also compared on its own (the same call on
+    a zero matrix, with copies of the pending factors).  `active` masks the workers of every update."""
+    import paper_1511_08486_amd as sfb
+    dev = "cuda:0"
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
+    if plan:
+        ctx.set_plan(**plan)
+    Wg = torch.from_numpy(wl.W0).to(dev)
+    U, V, loss = alloc_factors(wl, dev)
+    Wo = wl.W0.astype(np.float64)
+    dev_batches = [to_device(wl, b, dev) for b in wl.batches]
+    worst = {"U": 0.0, "V": 0.0, "W": 0.0, "loss": 0.0, "dW": 0.0}
+
+    def check(t, Uo, Vo, fo, what):
+        worst["U"] = max(worst["U"], assert_close(U.cpu().numpy(), Uo, tol, f"U {what}"))
+        worst["V"] = max(worst["V"], assert_close(V.float().cpu().numpy(), Vo, tol, f"V {what}"))
+        worst["W"] = max(worst["W"], assert_close(Wg.cpu().numpy(), Wo, tol, f"W {what}"))
+        worst["loss"] = max(worst["loss"], assert_close(loss.cpu().numpy(), fo, tol, f"loss {what}"))
+
+    db, dy = dev_batches[0]
+    ctx.compute_factors(Wg, db, dy, U, V, loss)
+    ctx.sync()
+    Uo, Vo, fo = oracle.factors(wl.model, Wo, wl.batch(0))
+    check(0, Uo, Vo, fo, "before the first update")
+    for t in range(1, steps + 1):
+        checked = t % check_every == 0 or t >= steps - 1
+        W_new = oracle.apply_update(Wo, oracle.delta_w(Uo, Vo, wl.P, wl.B, active), wl.eta)
+        if t < steps:
+            db, dy = dev_batches[t % len(dev_batches)]
+            if checked:
+                # the update this call applies, on its own: same call, zero matrix, copies of the pending factors
+                Wz, U2, V2 = torch.zeros_like(Wg), U.clone(), V.clone()
+                ctx.update_and_next_factors(Wz, U2, V2, db, dy, wl.eta, active=active)
+                ctx.sync()
+                mag = wl.eta * oracle.delta_w(np.abs(Uo), np.abs(Vo), wl.P, wl.B, active)
+                worst["dW"] = max(worst["dW"], assert_close(Wz.cpu().numpy(), W_new - Wo, tol, f"-eta*dW of call {t}", terms=mag))
+                del Wz, U2, V2, mag
+            ctx.update_and_next_factors(Wg, U, V, db, dy, wl.eta, loss=loss, active=active)
+            ctx.sync()
+            Wo = W_new
+            Uo, Vo, fo = oracle.factors(wl.model, Wo, wl.batch(t))
+            if checked:
+                check(t, Uo, Vo, fo, f"after call {t}")
+        else:
+            ctx.reconstruct_apply(Wg, U, V, wl.eta, active=active)
+            ctx.sync()
+            Wo = W_new
+            worst["W"] = max(worst["W"], assert_close(Wg.cpu().numpy(), Wo, tol, "W after the last update"))
+        if progress:
+            progress(f"{wl.name}: pipelined call {t}/{steps}" + (f" checked, worst error/allowance so far {worst}" if checked else ""))
+    info = ctx.pipeline_info()
+    ctx.close()
+    return worst, info

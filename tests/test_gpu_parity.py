@@ -507,11 +507,13 @@ def test_csr_columns_in_any_order_within_a_row(sfb, dense_scores):
     run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else None)
 
 
-@pytest.mark.parametrize("dense_scores", [False, True])
-def test_csr_column_repeated_inside_a_row_counts_as_the_sum_of_its_values(sfb, dense_scores):
+@pytest.mark.parametrize("dense_scores,D,density", [(False, 320, 0.05), (True, 320, 0.05), (False, 16500, 0.002)])
+def test_csr_column_repeated_inside_a_row_counts_as_the_sum_of_its_values(sfb, dense_scores, D, density):
     """The header defines it: a column that appears twice in a row contributes the sum of its values,
-    in the scores (from the stored entries or from the dense rows) and in v_i alike."""
-    wl = workloads.make("l2svm", seed=21, J=52, D=320, P=3, B=10, density=0.05, steps=2, pool=2)
+    in the scores (from the stored entries or from the dense rows) and in v_i alike.  D = 16500: a row
+    no longer fits the LDS buffer the dense rows are built in (the entries are added in memory) nor do
+    four rows of W fit for the scores from the stored entries (dense scores on the densified rows)."""
+    wl = workloads.make("l2svm", seed=21, J=52, D=D, P=3, B=10, density=density, steps=2, pool=2)
     rng = np.random.default_rng(21)
     for b in wl.batches:
         per = int(b["rowptr"][1])
