@@ -17,16 +17,19 @@
 // Work split of the 8 wavefronts (two per SIMD):
 //   phase 1  wavefront (rb, kh): rows 32*rb.. of the band x the tile's 32 columns, over half kh of the
 //            factor pairs.  A operand: its 32 rows of (alpha u)^T for its half, held in registers for
-//            the workgroup's whole life (loaded once).  B operand: v^T tile from LDS.  The kh = 1
-//            partial sums go to the kh = 0 wavefront of the same rows through LDS, which adds them in a
-//            fixed order (own + partner): results do not depend on timing.
+//            the workgroup's whole life (loaded once).  B operand: v^T tile from LDS.  The two wavefronts
+//            of a row block trade partial sums through LDS and each finishes two of the block's four row
+//            groups, adding in one fixed order ((kh = 0 part) + (kh = 1 part), then W): results do not
+//            depend on timing.
 //   phase 2  wavefront (rbp, nq): rows 64*rbp.. of the band (two 32-row blocks) x a quarter nq of the
 //            samples.  A operand: next features from LDS; B operand: the parked bf16 tile.
-// Memory traffic of a tile: v^T tile and feature tile arrive by LDS-DMA (issued by the kh = 1
-// wavefronts, two stages each in flight, completion counted by hand), the W tile by ordinary loads
-// of the kh = 0 wavefronts one tile ahead, in the accumulator layout (a wavefront instruction covers
-// two whole 128-byte lines).  Both DMA sources were laid out tile by tile, already swizzled, by the
-// packing kernels below, so a stage is one linear copy.
+// Memory traffic of a tile: the v^T tile and the feature tile (two stages each) and the fp32 W tile (one
+// stage) arrive by LDS-DMA, a share per wavefront, completion counted by hand; the new W entries are
+// stored from the accumulator layout (a wavefront instruction covers two whole 128-byte lines).  The
+// v^T and feature sources were laid out tile by tile, already swizzled, by the packing kernels below,
+// so a stage is one linear copy.
+#include <type_traits>
+
 #include "sfb_device.h"
 #include "sfb_kernels.h"
 
@@ -52,12 +55,19 @@ __device__ __forceinline__ void fu_barrier() { asm volatile("s_waitcnt lgkmcnt(0
 __host__ __device__ __forceinline__ int fu_key8(int r) { return (r >> 1) & 7; }
 __host__ __device__ __forceinline__ int fu_key4(int r) { return (r >> 2) & 3; }
 
-template <int N4> __device__ __forceinline__ void fu_wait_vm_case(int n) {
-    if (n >= 4 * N4) { wait_vmcnt<4 * N4>(); return; }
-    if constexpr (N4 > 0) fu_wait_vm_case<N4 - 1>(n);
+// At most n of this wavefront's vector-memory operations may still be in flight (n <= 40).
+__device__ __forceinline__ void fu_wait_vm(int n) {
+    switch (n) {
+#define FU_CASE(k) case k: wait_vmcnt<k>(); break;
+        FU_CASE(0) FU_CASE(1) FU_CASE(2) FU_CASE(3) FU_CASE(4) FU_CASE(5) FU_CASE(6) FU_CASE(7) FU_CASE(8) FU_CASE(9)
+        FU_CASE(10) FU_CASE(11) FU_CASE(12) FU_CASE(13) FU_CASE(14) FU_CASE(15) FU_CASE(16) FU_CASE(17) FU_CASE(18)
+        FU_CASE(19) FU_CASE(20) FU_CASE(21) FU_CASE(22) FU_CASE(23) FU_CASE(24) FU_CASE(25) FU_CASE(26) FU_CASE(27)
+        FU_CASE(28) FU_CASE(29) FU_CASE(30) FU_CASE(31) FU_CASE(32) FU_CASE(33) FU_CASE(34) FU_CASE(35) FU_CASE(36)
+        FU_CASE(37) FU_CASE(38) FU_CASE(39)
+#undef FU_CASE
+        default: wait_vmcnt<40>(); break;
+    }
 }
-// At most n vector-memory operations of this wavefront may still be in flight (n a multiple of 4, capped at 40).
-__device__ __forceinline__ void fu_wait_vm(int n) { fu_wait_vm_case<10>(n); }
 
 template <int NQ>   // N = 128 * NQ factor pairs (and next samples)
 __global__ __launch_bounds__(kFuThreads) void update_score_kernel(
@@ -66,11 +76,11 @@ __global__ __launch_bounds__(kFuThreads) void update_score_kernel(
     int n_bands, int total) {
     constexpr int N = 128 * NQ;
     constexpr int STAGE = 64 * N;                  // bytes of a v^T tile (32 x N bf16) = bytes of a feature tile (N x 32 bf16)
-    constexpr int LD = STAGE / 16 / 256;           // DMA instructions per loader lane and v^T / feature stage
-    constexpr int W_LD = kFuBand * 8 / 256;        // ... and per W tile (128 rows x 128 bytes)
+    constexpr int LD = STAGE / 16 / kFuThreads;    // DMA instructions per lane and v^T / feature stage
+    constexpr int W_LD = kFuBand * 8 / kFuThreads; // ... and per W tile (128 rows x 128 bytes)
     constexpr int KS1 = 4 * NQ;                    // 16-deep MFMA steps over a wavefront's half of the pairs
-    // LDS: two v^T stages, two feature stages, one fp32 W tile, and the exchange area of the partial sums, whose
-    // first half per row block is reused for the parked bf16 tile once the partial sums have been read
+    // LDS: two v^T stages, two feature stages, one fp32 W tile, and the exchange area of the partial sums
+    // (2 KB per wavefront), which is reused for the parked bf16 tile once the partial sums have been read
     constexpr int VT_OFF = 0, AN_OFF = 2 * STAGE, WS_OFF = 4 * STAGE, X_OFF = WS_OFF + kFuBand * 128;
     constexpr int TILE_ELEMS = 32 * N;             // bf16 elements of a packed tile
 
@@ -79,9 +89,8 @@ __global__ __launch_bounds__(kFuThreads) void update_score_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront-uniform: roles and counters live in scalar registers
     const int l32 = lane & 31, half = lane >> 5;
-    const int rb = wave & 3, kh = wave >> 2;       // phase 1 role
+    const int rb = wave & 3, kh = wave >> 2;       // phase 1 / update role
     const int rbp = wave & 1, nq = wave >> 1;      // phase 2 role
-    const bool loader = kh == 1;
 
     const int id = xcd_contiguous_id(blockIdx.x, total);    // a die's workgroups share a column slice: its
     const int band = id % n_bands, ks = id / n_bands;       // v^T and feature tiles are fetched once per die
@@ -97,35 +106,38 @@ __global__ __launch_bounds__(kFuThreads) void update_score_kernel(
         for (int s = 0; s < KS1; ++s) ut[s] = *reinterpret_cast<const u32x4*>(up + 16 * s);
     }
 
-    // ---- loader wavefronts (kh = 1): every stage copy is theirs, so their vector-memory counter sees loads
-    // only, which retire in order; `issued` counts their copies, a stage's mark is the count just after it ----
+    // ---- stage copies (LDS-DMA), issued by every wavefront: lane t moves the 16-byte items t, t + 512, ... of a
+    // stage.  A wavefront's loads retire in order, so "all but the n most recent loads have landed" is what
+    // s_waitcnt vmcnt(n) gives; `issued` counts this wavefront's copy instructions and a stage's mark is the
+    // count just after its copy.  The W stores of the same wavefronts also sit in that counter: they can only
+    // make a wait longer, never let it pass early (a load that has not landed keeps every younger load in
+    // flight, so more than n operations are outstanding). ----
     const uint32_t lds0 = (uint32_t)(uintptr_t)fu_lds;
-    const int lt = tid - 256;                      // loader lane 0..255
     int issued = 0, mark_vt[2] = {0, 0}, mark_an[2] = {0, 0}, mark_w = 0;
     auto issue = [&](const bf16_t* tile, int lds_off) {     // one linear copy of STAGE bytes
-        const unsigned char* g = reinterpret_cast<const unsigned char*>(tile) + lt * 16;
-        const uint32_t base = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)lds_off + (uint32_t)((wave - 4) * 1024));
+        const unsigned char* g = reinterpret_cast<const unsigned char*>(tile) + tid * 16;
+        const uint32_t base = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)lds_off + (uint32_t)(wave * 1024));
 #pragma unroll
-        for (int i = 0; i < LD; ++i) fu_dma16(g + i * 4096, base + (uint32_t)(i * 4096));
+        for (int i = 0; i < LD; ++i) fu_dma16(g + i * (kFuThreads * 16), base + (uint32_t)(i * kFuThreads * 16));
         issued += LD;
     };
-    // W tile: slot = lt + 256 i -> row slot / 8 of the band, 16-byte item slot % 8; rows beyond J (last band)
-    // are read from row J - 1 and never stored.  Offsets are 32-bit (host: J * ldw < 2^31).
-    const int w_row0 = j0 + (lt >> 3);
-    const uint32_t w_col = (uint32_t)(k0 + 4 * (lt & 7));
+    // W tile: item t + 512 i -> row (t + 512 i) / 8 of the band, 16 bytes at column 4 * (t % 8); rows beyond J
+    // (last band) are read from row J - 1 and never stored.  Offsets are 32-bit (host: J * ldw < 2^31).
+    const int w_row0 = j0 + (tid >> 3);
+    const uint32_t w_col = (uint32_t)(k0 + 4 * (tid & 7));
     auto issue_w = [&](int tile) {
-        const uint32_t base = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)WS_OFF + (uint32_t)((wave - 4) * 1024));
+        const uint32_t base = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)WS_OFF + (uint32_t)(wave * 1024));
 #pragma unroll
         for (int i = 0; i < W_LD; ++i)
-            fu_dma16(W + ((uint32_t)min(w_row0 + 32 * i, J - 1) * (uint32_t)ldw + w_col + (uint32_t)(tile * kFuCols)),
-                     base + (uint32_t)(i * 4096));
+            fu_dma16(W + ((uint32_t)min(w_row0 + 64 * i, J - 1) * (uint32_t)ldw + w_col + (uint32_t)(tile * kFuCols)),
+                     base + (uint32_t)(i * kFuThreads * 16));
         issued += W_LD;
         mark_w = issued;
     };
 
-    // W stores of the kh = 0 wavefronts, accumulator layout: acc[e] <-> row 8*(e/4) + 4*half + e%4, column l32
-    // Address = (wavefront-uniform row pointer) + (one 32-bit lane offset shared by all 16 stores).  Only the
-    // last band can be ragged: whether this wavefront's 32 rows all exist is wavefront-uniform.
+    // W stores, accumulator layout: acc[e] <-> row 8*(e/4) + 4*half + e%4 of the row block, column l32.
+    // Address = (wavefront-uniform row pointer) + (one 32-bit lane offset shared by all stores).  Only the last
+    // band can be ragged: whether this wavefront's 32 rows all exist is wavefront-uniform.
     float* const wblock = W + (int64_t)(j0 + 32 * rb) * ldw + k0;
     const uint32_t wlane = (uint32_t)(4 * half) * (uint32_t)ldw + (uint32_t)l32;
     const bool wfull = J - (j0 + 32 * rb) >= 32;
@@ -144,29 +156,68 @@ __global__ __launch_bounds__(kFuThreads) void update_score_kernel(
     const int f4 = fu_key4(l32);
     const int it4[2] = {((0 + half) ^ f4) * 16, ((2 + half) ^ f4) * 16};
 
-    if (loader) {
-        issue(VTp + (int64_t)t0 * TILE_ELEMS, VT_OFF);
-        mark_vt[0] = issued;
-        issue(AnP + (int64_t)t0 * TILE_ELEMS, AN_OFF);
-        mark_an[0] = issued;
-        issue_w(0);
-        if (n_tiles > 1) {
-            issue(VTp + (int64_t)(t0 + 1) * TILE_ELEMS, VT_OFF + STAGE);
-            mark_vt[1] = issued;
-        }
+    issue(VTp + (int64_t)t0 * TILE_ELEMS, VT_OFF);
+    mark_vt[0] = issued;
+    issue(AnP + (int64_t)t0 * TILE_ELEMS, AN_OFF);
+    mark_an[0] = issued;
+    issue_w(0);
+    if (n_tiles > 1) {
+        issue(VTp + (int64_t)(t0 + 1) * TILE_ELEMS, VT_OFF + STAGE);
+        mark_vt[1] = issued;
     }
+
+    // The update of the entries this wavefront finishes: acc[8*KH .. 8*KH + 7] (two of the four row groups);
+    // the partner's partial sums of the same entries come through LDS.  `own + partner` is formed as
+    // (kh = 0 part) + (kh = 1 part) by both wavefronts of a pair, then added to W: one fixed order of additions.
+    // The new entries are stored, and parked as bf16 [row][32 columns] over the partner's exchange slot, which
+    // only this wavefront reads: neighbouring lanes hold neighbouring columns, so a lane pair trades one value
+    // and each lane writes one packed pair (even lane: the row of e, odd lane: the row of e + 1).
+    auto finish = [&](auto KHc, const f32x16& acc, int tile) {
+        constexpr int KH = decltype(KHc)::value;
+        const unsigned char* slot = fu_lds + X_OFF + rb * 4096 + (1 - KH) * 2048;
+        f32x4 p[2];
+        float w[8];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) p[j] = *reinterpret_cast<const f32x4*>(slot + j * 1024 + lane * 16);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int rl = 8 * (2 * KH + t / 4) + (t % 4);                       // + 4*half: row of the block
+            w[t] = *reinterpret_cast<const float*>(fu_lds + WS_OFF + (32 * rb + rl + 4 * half) * 128 + l32 * 4);
+        }
+        const bool odd = lane & 1;
+        const int pair = l32 >> 1;                                               // dword of the 64-byte row
+        unsigned char* park = fu_lds + X_OFF + rb * 4096 + (1 - KH) * 2048;
+#pragma unroll
+        for (int t = 0; t < 8; t += 2) {
+            float wn[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int e = 8 * KH + t + u, c = 8 * (e / 4) + (e % 4);
+                wn[u] = w[t + u] + (acc[e] + p[(t + u) / 4][(t + u) % 4]);
+                float* const wrowp = wblock + (int64_t)c * ldw + tile * kFuCols;      // uniform
+                if (wfull || c < wlim) wrowp[wlane] = wn[u];
+            }
+            const float send = odd ? wn[0] : wn[1];
+            const float recv = __builtin_bit_cast(
+                float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));   // lane ^ 1
+            const uint32_t pk = odd ? cvt_pk_bf16(recv, wn[1]) : cvt_pk_bf16(wn[0], recv);
+            const int rl = 8 * (2 * KH + t / 4) + 4 * half + (t % 4) + (odd ? 1 : 0);     // row of the block
+            const int off = (rl & 15) * 64 + (((pair >> 2) ^ fu_key4(rl)) * 16) + (pair & 3) * 4;
+            *reinterpret_cast<uint32_t*>(park + off) = pk;
+        }
+    };
 
     for (int i = 0; i < n_tiles; ++i) {
         const int st = i & 1;
         // ---- the v^T tile of this step has landed; everybody is done with the previous step's feature tile ----
-        if (loader) fu_wait_vm(issued - mark_vt[st]);
+        fu_wait_vm(issued - mark_vt[st]);
         fu_barrier();
-        if (loader && i + 1 < n_tiles) {
+        if (i + 1 < n_tiles) {
             issue(AnP + (int64_t)(t0 + i + 1) * TILE_ELEMS, AN_OFF + (st ^ 1) * STAGE);
             mark_an[st ^ 1] = issued;
         }
 
-        // ---- phase 1: this wavefront's half of the contraction over the factor pairs ----
+        // ---- phase 1: this wavefront's half of the contraction over the factor pairs; fragments four steps ahead ----
         f32x16 acc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
@@ -175,78 +226,54 @@ __global__ __launch_bounds__(kFuThreads) void update_score_kernel(
             auto frag = [&](int s) {
                 return *reinterpret_cast<const u32x4*>(vt + (s >> 2) * 4096 + (((2 * (s & 3)) * 16) ^ hk8));
             };
-            u32x4 b0 = frag(0), b1;
+            u32x4 fr[4];
 #pragma unroll
-            for (int s = 0; s < KS1; s += 2) {
-                b1 = frag(s + 1);
+            for (int s = 0; s < 4; ++s) fr[s] = frag(s);
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) {
                 __builtin_amdgcn_sched_barrier(0);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(fu_bf16x8, ut[s]),
-                                                              __builtin_bit_cast(fu_bf16x8, b0), acc, 0, 0, 0);
-                if (s + 2 < KS1) b0 = frag(s + 2);
-                __builtin_amdgcn_sched_barrier(0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(fu_bf16x8, ut[s + 1]),
-                                                              __builtin_bit_cast(fu_bf16x8, b1), acc, 0, 0, 0);
+                                                              __builtin_bit_cast(fu_bf16x8, fr[s & 3]), acc, 0, 0, 0);
+                if (s + 4 < KS1) fr[s & 3] = frag(s + 4);
             }
         }
-        if (kh == 1) {
+        // the partner finishes the other two row groups: hand it this wavefront's partial sums of those
+        {
+            unsigned char* mine = fu_lds + X_OFF + rb * 4096 + kh * 2048;
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *reinterpret_cast<f32x4*>(fu_lds + X_OFF + rb * 4096 + q * 1024 + lane * 16) =
-                    f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+            for (int j = 0; j < 2; ++j) {
+                const int e0 = kh == 0 ? 8 + 4 * j : 4 * j;
+                *reinterpret_cast<f32x4*>(mine + j * 1024 + lane * 16) =
+                    kh == 0 ? f32x4{acc[8 + 4 * j], acc[9 + 4 * j], acc[10 + 4 * j], acc[11 + 4 * j]}
+                            : f32x4{acc[4 * j], acc[1 + 4 * j], acc[2 + 4 * j], acc[3 + 4 * j]};
+                (void)e0;
+            }
         }
         // ---- partial sums exchanged, the W tile has landed; the v^T stage is free again ----
-        if (loader) fu_wait_vm(issued - mark_w);
+        fu_wait_vm(issued - mark_w);
         fu_barrier();
-        if (loader && i + 2 < n_tiles) {
+        if (i + 2 < n_tiles) {
             issue(VTp + (int64_t)(t0 + i + 2) * TILE_ELEMS, VT_OFF + st * STAGE);
             mark_vt[st] = issued;
         }
+        if (kh == 0) finish(std::integral_constant<int, 0>{}, acc, i);
+        else finish(std::integral_constant<int, 1>{}, acc, i);
 
-        if (kh == 0) {
-            // Four rows at a time: own half + partner's half, then W (one fixed order of additions); store the new
-            // entries; park them as bf16 [row][32 columns] where this row block's partial sums were.  Neighbouring
-            // lanes hold neighbouring columns, so a lane pair trades one value and each lane writes one packed pair
-            // (even lane: the row of e, odd lane: the row of e + 1).
-            const bool odd = lane & 1;
-            const int pair = l32 >> 1;                                                // dword of the 64-byte row
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x4 p = *reinterpret_cast<const f32x4*>(fu_lds + X_OFF + rb * 4096 + q * 1024 + lane * 16);
-                float wn[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float w = *reinterpret_cast<const float*>(fu_lds + WS_OFF + (32 * rb + 8 * q + 4 * half + r) * 128 + l32 * 4);
-                    wn[r] = w + (acc[4 * q + r] + p[r]);
-                    const int c = 8 * q + r;
-                    float* const wrowp = wblock + (int64_t)c * ldw + i * kFuCols;        // uniform
-                    if (wfull || c < wlim) wrowp[wlane] = wn[r];
-                }
-#pragma unroll
-                for (int r = 0; r < 4; r += 2) {
-                    const float send = odd ? wn[r] : wn[r + 1];
-                    const float recv = __builtin_bit_cast(
-                        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));   // lane ^ 1
-                    const uint32_t pk = odd ? cvt_pk_bf16(recv, wn[r + 1]) : cvt_pk_bf16(wn[r], recv);
-                    const int row = 8 * q + 4 * half + r + (odd ? 1 : 0);             // within the row block
-                    const int off = row * 64 + (((pair >> 2) ^ fu_key4(row)) * 16) + (pair & 3) * 4;
-                    *reinterpret_cast<uint32_t*>(fu_lds + X_OFF + rb * 4096 + off) = pk;
-                }
-            }
-        }
         // ---- the parked tile is complete, the W stage is free, and the feature tile has landed ----
-        if (loader) fu_wait_vm(issued - mark_an[st]);
+        fu_wait_vm(issued - mark_an[st]);
         fu_barrier();
-        if (loader && i + 1 < n_tiles) issue_w(i + 1);
+        if (i + 1 < n_tiles) issue_w(i + 1);
 
         // ---- phase 2: scores of the next batch from the new tile ----
         {
             const unsigned char* an = fu_lds + AN_OFF + st * STAGE + (nq * NQ * 32 + l32) * 64;
+            // row l32 of a block was parked by the wavefront that finished its row group, over its partner's slot
+            const unsigned char* parked = fu_lds + X_OFF + (2 * rbp) * 4096 + (1 - (l32 >> 4)) * 2048 + (l32 & 15) * 64;
 #pragma unroll
             for (int s = 0; s < 2; ++s) {          // 16 columns at a time: two fragments of the new tile, NQ of the features
                 u32x4 wf[2];
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
-                    wf[a] = *reinterpret_cast<const u32x4*>(fu_lds + X_OFF + (2 * rbp + a) * 4096 + l32 * 64 + it4[s]);
+                for (int a = 0; a < 2; ++a) wf[a] = *reinterpret_cast<const u32x4*>(parked + a * 4096 + it4[s]);
                 u32x4 a0 = *reinterpret_cast<const u32x4*>(an + it4[s]), a1;
 #pragma unroll
                 for (int b = 0; b < NQ; b += 2) {
