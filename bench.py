@@ -319,6 +319,17 @@ def measure_floors(sfb, torch, big_wl=None, big_W0=None):
             us = timed(ctx, lambda: ctx.probe(kind, param=wps), 3)
             total = flop * 16 * iters * 256 * 4 * wps
             floors[f"{kind}_loop_{wps}_wavefronts_per_simd"] = {"TFLOP/s": total / (us * 1e-6) / 1e12, "us_per_launch": us}
+    # an empty kernel: the dispatch cost under every launch-bound kernel (factor u at the small configurations);
+    # back to back on the stream (wall clock over 200 launches) and from its own dispatch events
+    us = timed(ctx, lambda: ctx.probe("empty"), 50)
+    ctx.probe("empty")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(200):
+        ctx.probe("empty")
+    torch.cuda.synchronize()
+    floors["empty_kernel"] = {"us_per_launch": us, "us_per_launch_back_to_back": (time.perf_counter() - t0) / 200 * 1e6,
+                              "note": "256 workgroups that do nothing"}
     ctx.close()
     if big_wl is not None:
         # bare W traffic of the 860 MB matrix in the access shapes of the bf16 kernels

@@ -341,6 +341,7 @@ SFB_API sfb_status sfb_stream_copy(sfb_ctx *ctx, void *dst, const void *src, siz
  *   SFB_PROBE_MFMA_F32  register-resident loop of v_mfma_f32_32x32x2_f32 on every compute unit, param = 1
  *   SFB_PROBE_MFMA_BF16 or 2 wavefronts per SIMD; 256 * 4 * param wavefronts run SFB_PROBE_MFMA_ITERS * 16
  *                       instructions each (4096 resp. 32768 flop per instruction); W is ignored.
+ *   SFB_PROBE_EMPTY     an empty kernel of 256 workgroups: what a dispatch costs (W and param ignored).
  * Needs a registered workspace (64 floats of it are scribbled on).  SFB_EINVAL: null W where one is
  * needed, param outside its range, unknown kind.
  */
@@ -348,7 +349,8 @@ typedef enum {
     SFB_PROBE_W_STREAM = 0,
     SFB_PROBE_W_RMW = 1,
     SFB_PROBE_MFMA_F32 = 2,
-    SFB_PROBE_MFMA_BF16 = 3
+    SFB_PROBE_MFMA_BF16 = 3,
+    SFB_PROBE_EMPTY = 4
 } sfb_probe_kind;
 #define SFB_PROBE_MFMA_ITERS 4000
 SFB_API sfb_status sfb_probe(sfb_ctx *ctx, sfb_probe_kind kind, float *W, int64_t ldw, int32_t param);

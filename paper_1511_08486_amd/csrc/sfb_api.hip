@@ -703,6 +703,11 @@ sfb_status sfb_probe(sfb_ctx* c, sfb_probe_kind kind, float* W, int64_t ldw, int
             e = launch_probe_mfma(kind == SFB_PROBE_MFMA_BF16, param, SFB_PROBE_MFMA_ITERS, (float*)c->ws, c->stream);
             break;
         }
+        case SFB_PROBE_EMPTY: {
+            Timed t(c, 3);
+            e = launch_probe_empty(c->stream);
+            break;
+        }
         default: return SFB_EINVAL;
     }
     if (e != hipSuccess) return hip_fail(c, e);

@@ -113,6 +113,7 @@ hipError_t launch_probe_w_stream(const float* W, int64_t ldw, int J, int D, int 
                                  hipStream_t s);
 hipError_t launch_probe_w_rmw(float* W, int64_t ldw, int J, int D, float add, hipStream_t s);
 hipError_t launch_probe_mfma(bool bf16, int waves_per_simd, int iters, float* sink, hipStream_t s);
+hipError_t launch_probe_empty(hipStream_t s);
 
 // Proximal step on W (Section 2.1).  kind: 0 identity, 1 squared l2 (param = lam), 2 l1
 // (param = lam), 3 projection of every column onto the l2 ball of radius param (needs

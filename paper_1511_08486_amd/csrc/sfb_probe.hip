@@ -9,6 +9,7 @@
 //   probe_w_rmw      W += c in the tile and lane mapping of the bf16 reconstruction's epilogue:
 //                    256 x 128 tiles, 2 x 2 wavefronts, the MFMA accumulator layout (lane = column,
 //                    16 rows per 32 x 32 block), four blocks of loads in flight
+//   probe_empty      an empty kernel: the cost of one dispatch
 //   probe_mfma       a register-resident loop of matrix-core instructions (no memory traffic):
 //                    the rate the matrix cores sustain at the clock the part holds under that load
 #include "sfb_device.h"
@@ -115,6 +116,14 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(float* __restrict__ sin
 #pragma unroll
         for (int e = 0; e < 16; ++e) s += acc[n][e];
     sink[(blockIdx.x * blockDim.x + threadIdx.x) % 64] = s;       // 64 floats of sink: last writer wins, value unused
+}
+
+// Nothing at all: what one dispatch costs on this stream (the floor of every launch-bound kernel).
+__global__ void probe_empty_kernel(int) {}
+
+hipError_t launch_probe_empty(hipStream_t s) {
+    SFB_LAUNCH(probe_empty_kernel, dim3(256), dim3(256), 0, s, 0);
+    return hipGetLastError();
 }
 
 hipError_t launch_probe_w_stream(const float* W, int64_t ldw, int J, int D, int k_slice, int dup, float* sink,
