@@ -252,12 +252,13 @@ __global__ __launch_bounds__(kFuThreads) void update_score_kernel(
         // ---- partial sums exchanged, the W tile has landed; the v^T stage is free again ----
         fu_wait_vm(issued - mark_w);
         fu_barrier();
+        if (kh == 0) finish(std::integral_constant<int, 0>{}, acc, i);
+        else finish(std::integral_constant<int, 1>{}, acc, i);
+        // (after the update's stores: this copy has two tiles of lead, the stores are wanted now)
         if (i + 2 < n_tiles) {
             issue(VTp + (int64_t)(t0 + i + 2) * TILE_ELEMS, VT_OFF + st * STAGE);
             mark_vt[st] = issued;
         }
-        if (kh == 0) finish(std::integral_constant<int, 0>{}, acc, i);
-        else finish(std::integral_constant<int, 1>{}, acc, i);
 
         // ---- the parked tile is complete, the W stage is free, and the feature tile has landed ----
         fu_wait_vm(issued - mark_an[st]);
