@@ -93,3 +93,23 @@ def test_fused_call_is_deterministic_and_misaligned_operands_fall_back():
     assert_close(U.cpu().numpy(), res[0][1].cpu().numpy(), 1e-3, "U, misaligned, against the fused result")
     assert float(buf[:, 0].abs().max()) == 0.0 and float(buf[:, wl.D + 1:].abs().max()) == 0.0
     ctx.close()
+
+
+def test_probes_leave_w_as_it_was_and_refuse_bad_arguments():
+    """The measurement aids run on real buffers: the read-modify-write probe adds zero (W keeps its bits), the
+    stream probe only reads; wrong parameters are refused with a status, nothing is launched."""
+    import paper_1511_08486_amd as sfb
+    dev = "cuda:0"
+    ctx = sfb.Sfb("mlr", 520, 1024, 4, 32, dtype="bf16", device=dev)
+    W = torch.randn((520, 1024), device=dev)
+    keep = W.clone()
+    for kind, param in (("w_stream", 1), ("w_stream", 2), ("w_rmw", 1), ("mfma_f32", 1), ("mfma_bf16", 2), ("empty", 1)):
+        ctx.probe(kind, W, param)
+    ctx.sync()
+    assert torch.equal(W, keep)
+    for kind, param in (("w_stream", 3), ("mfma_f32", 0), ("mfma_bf16", 5)):
+        with pytest.raises(sfb.SfbError):
+            ctx.probe(kind, W, param)
+    with pytest.raises(sfb.SfbError):
+        ctx.probe("w_rmw", None)
+    ctx.close()

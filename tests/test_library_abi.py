@@ -279,3 +279,39 @@ def test_noalloc_step_rejects_what_its_fixed_scratch_cannot_hold(lib):
     assert lib.sfb_step_noalloc(ctx, None, 21504, C.byref(b), fake, fake, 10000, fake, 21504, None, 0.1, None) == -1
     assert lib.sfb_step_noalloc(ctx, fake, 21503, C.byref(b), fake, fake, 10000, fake, 21504, None, 0.1, None) == -2
     lib.sfb_destroy(ctx)
+
+
+def test_pipelined_step_and_probes_validate_their_arguments(lib):
+    """Fake non-null pointers are safe here: every call below is refused before anything is launched."""
+    import paper_1511_08486_amd as sfb
+    for name in ("sfb_step_pipelined", "sfb_pipeline_info", "sfb_probe", "sfb_default_scale"):
+        assert name in declared_symbols()
+    fake = C.c_void_p(0x1000)
+    b = sfb.binding.sfb_batch()
+    b.a, b.lda = 0x1000, 1024
+    ctx = C.c_void_p()
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 300, 1024, 4, 32, sfb.SFB_BF16, None) == 0
+    fused, grid, slices = C.c_int32(), C.c_int32(), C.c_int32()
+    assert lib.sfb_pipeline_info(ctx, C.byref(fused), C.byref(grid), C.byref(slices)) == 0
+    assert fused.value == 1 and grid.value == 3 * slices.value and slices.value >= 1      # 3 bands of 128 rows
+    scale = C.c_float()
+    assert lib.sfb_default_scale(ctx, C.byref(scale)) == 0 and scale.value == 1.0 / 32
+    assert lib.sfb_default_scale(ctx, None) == -1
+    # argument checks of the pipelined step: null W, short leading dimension, missing batch, bad eta; then no workspace
+    args = lambda W, ldw, batch, eta: lib.sfb_step_pipelined(ctx, W, ldw, fake, 300, fake, 1024, batch, fake, None, eta, None)
+    assert args(None, 1024, C.byref(b), 0.1) == -1
+    assert args(fake, 1023, C.byref(b), 0.1) == -2
+    assert args(fake, 1024, None, 0.1) == -1
+    assert args(fake, 1024, C.byref(b), float("nan")) == -1
+    assert args(fake, 1024, C.byref(b), 0.1) == -5
+    # probes: no workspace registered -> refused; unknown kind and bad parameters are refused too
+    assert lib.sfb_probe(ctx, 2, None, 0, 1) == -5
+    assert lib.sfb_probe(None, 2, None, 0, 1) == -1
+    lib.sfb_destroy(ctx)
+    # shapes the one-pass kernel does not take report so
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 300, 1004, 3, 30, sfb.SFB_BF16, None) == 0
+    assert lib.sfb_pipeline_info(ctx, C.byref(fused), None, None) == 0 and fused.value == 0
+    lib.sfb_destroy(ctx)
+    assert lib.sfb_create(C.byref(ctx), sfb.SFB_MLR, 1000, 4096, 8, 64, sfb.SFB_F32, None) == 0
+    assert lib.sfb_pipeline_info(ctx, C.byref(fused), None, None) == 0 and fused.value == 0
+    lib.sfb_destroy(ctx)
