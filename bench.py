@@ -347,6 +347,13 @@ def measure_floors(sfb, torch, big_wl=None, big_W0=None):
             "us_per_launch": us, "GB/s": 2.0 * wbytes / (us * 1e-6) / 1e9,
             "note": "W += 0 in the bf16 reconstruction's tile and lane mapping (256 x 128 tiles, accumulator layout)"}
         assert torch.equal(W, big_W0), "the read-modify-write probe must leave W as it was"
+        if c2.pipeline_info()["fused"]:
+            us = timed(c2, lambda: c2.probe("fused_traffic", W), 5)
+            floors["one_pass_kernel_traffic_only"] = {
+                "us_per_launch": us,
+                "note": "the one-pass update + score kernel's own copies and stores (same grid, tiles, addresses and "
+                        "instructions), no matrix work, no barriers: what the memory path alone takes for that traffic"}
+            assert torch.equal(W, big_W0), "the traffic probe must leave W as it was"
         c2.close()
     return floors
 

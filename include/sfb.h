@@ -342,6 +342,13 @@ SFB_API sfb_status sfb_stream_copy(sfb_ctx *ctx, void *dst, const void *src, siz
  *   SFB_PROBE_MFMA_BF16 or 2 wavefronts per SIMD; 256 * 4 * param wavefronts run SFB_PROBE_MFMA_ITERS * 16
  *                       instructions each (4096 resp. 32768 flop per instruction); W is ignored.
  *   SFB_PROBE_EMPTY     an empty kernel of 256 workgroups: what a dispatch costs (W and param ignored).
+ *   SFB_PROBE_FUSED_TRAFFIC  the memory operations of sfb_step_pipelined's one-pass kernel and nothing else, in
+ *                       its grid: per tile of 128 rows x 32 columns the copies of the packed v^T and
+ *                       feature tiles and of the W tile into LDS and the stores of the W tile (the values
+ *                       just read: W keeps its bits); no matrix work, no barriers.  For contexts whose
+ *                       sfb_pipeline_info says fused, W 16-byte aligned with ldw % 4 == 0 (else
+ *                       SFB_EUNSUPPORTED); needs the whole registered workspace (its packed-operand areas
+ *                       are read, whatever they hold); param ignored.
  * Needs a registered workspace (64 floats of it are scribbled on).  SFB_EINVAL: null W where one is
  * needed, param outside its range, unknown kind.
  */
@@ -350,7 +357,8 @@ typedef enum {
     SFB_PROBE_W_RMW = 1,
     SFB_PROBE_MFMA_F32 = 2,
     SFB_PROBE_MFMA_BF16 = 3,
-    SFB_PROBE_EMPTY = 4
+    SFB_PROBE_EMPTY = 4,
+    SFB_PROBE_FUSED_TRAFFIC = 5
 } sfb_probe_kind;
 #define SFB_PROBE_MFMA_ITERS 4000
 SFB_API sfb_status sfb_probe(sfb_ctx *ctx, sfb_probe_kind kind, float *W, int64_t ldw, int32_t param);

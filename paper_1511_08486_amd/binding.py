@@ -319,7 +319,7 @@ class Sfb:
         nbytes = src.numel() * src.element_size()
         self._check(lib.sfb_stream_copy(self._ctx, dst.data_ptr(), src.data_ptr(), nbytes), "sfb_stream_copy")
 
-    PROBES = {"w_stream": 0, "w_rmw": 1, "mfma_f32": 2, "mfma_bf16": 3, "empty": 4}
+    PROBES = {"w_stream": 0, "w_rmw": 1, "mfma_f32": 2, "mfma_bf16": 3, "empty": 4, "fused_traffic": 5}
     PROBE_MFMA_ITERS = 4000
 
     def probe(self, kind, W=None, param=1):

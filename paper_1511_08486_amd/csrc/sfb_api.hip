@@ -708,6 +708,20 @@ sfb_status sfb_probe(sfb_ctx* c, sfb_probe_kind kind, float* W, int64_t ldw, int
             e = launch_probe_empty(c->stream);
             break;
         }
+        case SFB_PROBE_FUSED_TRAFFIC: {
+            if (!W) return SFB_EINVAL;
+            if (ldw < c->D) return SFB_ESHAPE;
+            // the shapes and operands the one-pass kernel takes, and its packed-operand areas of the workspace
+            const int N = c->P * c->B;
+            if (!c->fused_ok || (int64_t)c->J * ldw >= (1LL << 31) || ((uintptr_t)W % 16) != 0 || (ldw % 4) != 0)
+                return SFB_EUNSUPPORTED;
+            if (c->ws_bytes < workspace_need(c)) return SFB_EWORKSPACE;
+            char* ws_factors = (char*)c->ws + scores_need(c);
+            char* ws_next = ws_factors + bf16_recon_workspace(c->J, c->D, N);
+            Timed t(c, 3);
+            e = launch_probe_fused_traffic(W, ldw, (int)c->J, (int)c->D, N, c->fused, ws_factors, ws_next, c->stream);
+            break;
+        }
         default: return SFB_EINVAL;
     }
     if (e != hipSuccess) return hip_fail(c, e);

@@ -114,6 +114,10 @@ hipError_t launch_probe_w_stream(const float* W, int64_t ldw, int J, int D, int 
 hipError_t launch_probe_w_rmw(float* W, int64_t ldw, int J, int D, float add, hipStream_t s);
 hipError_t launch_probe_mfma(bool bf16, int waves_per_simd, int iters, float* sink, hipStream_t s);
 hipError_t launch_probe_empty(hipStream_t s);
+struct FusedPlan;
+// ws_factors / ws_next: where launch_fused keeps its packed operands (their contents do not matter here)
+hipError_t launch_probe_fused_traffic(float* W, int64_t ldw, int J, int D, int N, const FusedPlan& p, const void* ws_factors,
+                                      const void* ws_next, hipStream_t s);
 
 // Proximal step on W (Section 2.1).  kind: 0 identity, 1 squared l2 (param = lam), 2 l1
 // (param = lam), 3 projection of every column onto the l2 ball of radius param (needs

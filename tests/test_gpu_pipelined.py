@@ -103,7 +103,8 @@ def test_probes_leave_w_as_it_was_and_refuse_bad_arguments():
     ctx = sfb.Sfb("mlr", 520, 1024, 4, 32, dtype="bf16", device=dev)
     W = torch.randn((520, 1024), device=dev)
     keep = W.clone()
-    for kind, param in (("w_stream", 1), ("w_stream", 2), ("w_rmw", 1), ("mfma_f32", 1), ("mfma_bf16", 2), ("empty", 1)):
+    for kind, param in (("w_stream", 1), ("w_stream", 2), ("w_rmw", 1), ("mfma_f32", 1), ("mfma_bf16", 2), ("empty", 1),
+                        ("fused_traffic", 0)):
         ctx.probe(kind, W, param)
     ctx.sync()
     assert torch.equal(W, keep)
@@ -112,4 +113,18 @@ def test_probes_leave_w_as_it_was_and_refuse_bad_arguments():
             ctx.probe(kind, W, param)
     with pytest.raises(sfb.SfbError):
         ctx.probe("w_rmw", None)
+    ctx.close()
+    # a ragged last band (J = 300: 44 rows of the third band) and a short matrix; a shape the one-pass kernel
+    # does not take is refused
+    for J, D, P, B in ((300, 1024, 2, 64), (40, 64, 4, 64)):
+        ctx = sfb.Sfb("mlr", J, D, P, B, dtype="bf16", device=dev)
+        W = torch.randn((J, D), device=dev)
+        keep = W.clone()
+        ctx.probe("fused_traffic", W)
+        ctx.sync()
+        assert torch.equal(W, keep)
+        ctx.close()
+    ctx = sfb.Sfb("mlr", 300, 1000, 2, 64, dtype="bf16", device=dev)
+    with pytest.raises(sfb.SfbError):
+        ctx.probe("fused_traffic", torch.zeros((300, 1000), device=dev))
     ctx.close()
