@@ -551,8 +551,9 @@ static const ReconVariant kReconVariants[] = {
     {1, 2, 1, true},   // 8: 64 x 128, 2 wavefronts, LDS-DMA staging (falls back to 1)
     {1, 2, 1, true},   // 9: 64 x 64, 4 wavefronts of one 32 x 32 block each, LDS-DMA staging (falls back to 8)
     {1, 4, 1, true},   // 10: as 7 with 16-pair stages and a register budget for two workgroups per compute unit
+    {1, 2, 1, true},   // 11: (96..160) x 64, 4 wavefronts = 2 column blocks x 2 halves of every stage's pairs (falls back to 9)
 };
-constexpr int kSmallVariant = 9;
+constexpr int kSmallVariant = 9, kKsplitVariant = 11;
 constexpr int kNumReconVariants = sizeof(kReconVariants) / sizeof(kReconVariants[0]);
 
 int num_reconstruct_variants() { return kNumReconVariants; }
@@ -589,7 +590,15 @@ ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
     // clearly more than its share (e.g. J = 600: 3 blocks instead of 4)
     if (kReconVariants[variant].dma) {
         const int bm = 32 * kReconVariants[variant].mt * kReconVariants[variant].nwr;
-        if (reconstruct_small_wins(J, D, bm, kReconVariants[variant].nwr)) variant = kSmallVariant;
+        const int nwr = kReconVariants[variant].nwr;
+        // whole 32 x 32 blocks (through all pairs) on the busiest SIMD with the choice so far
+        int64_t busiest = (((J + bm - 1) / bm) * ((D + kReconBN - 1) / kReconBN) * nwr + 1023) / 1024 * 4;
+        if (reconstruct_small_wins(J, D, bm, nwr)) {
+            variant = kSmallVariant;
+            busiest = (((J + 63) / 64) * (D / 64) * 4 + 1023) / 1024;
+        }
+        // splitting the pairs as well where that evens the load out further (J = 600: 2.5 instead of 3)
+        if (reconstruct_ksplit_wins(J, D, busiest)) variant = kKsplitVariant;
     }
     return plan_reconstruct_variant(J, D, variant);
 }
@@ -597,8 +606,8 @@ ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
 ReconPlan plan_reconstruct_variant(int64_t J, int64_t D, int variant) {
     ReconPlan p;
     p.variant = variant;
-    p.bm = 32 * kReconVariants[variant].mt * kReconVariants[variant].nwr;
-    p.bn = variant == kSmallVariant ? 64 : kReconBN;
+    p.bm = variant == kKsplitVariant ? reconstruct_ksplit_rows(J) : 32 * kReconVariants[variant].mt * kReconVariants[variant].nwr;
+    p.bn = (variant == kSmallVariant || variant == kKsplitVariant) ? 64 : kReconBN;
     p.grid = (int)(((J + p.bm - 1) / p.bm) * ((D + p.bn - 1) / p.bn));
     return p;
 }
@@ -651,7 +660,11 @@ static hipError_t launch_recon_v(const ReconArgs& a, const ReconPlan& p, hipStre
 
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s) {
     ReconPlan q = p;
-    if (p.variant == kSmallVariant) {
+    if (p.variant == kKsplitVariant) {
+        if (reconstruct_ksplit_ok(a)) return launch_reconstruct_ksplit(a, s);
+        q.variant = kSmallVariant;
+    }
+    if (q.variant == kSmallVariant) {
         if (reconstruct_small_ok(a)) return launch_reconstruct_small(a, s);
         q.variant = 8;
     }

@@ -78,11 +78,32 @@ def test_single_block_reconstruct_variant(sfb, J, D, P, B):
     run_chain(wl, 3, TOL32, plan=dict(recon_variant=9))
 
 
-def test_single_block_variant_is_what_the_plan_picks_for_600_rows_and_falls_back_when_it_must(sfb):
+@pytest.mark.parametrize("J,D,P,B", [(600, 4096, 8, 128), (388, 1024, 4, 48), (256, 256, 1, 32), (96, 64, 2, 32),
+                                     (352, 192, 3, 32), (68, 64, 1, 128), (1000, 4096, 8, 64), (440, 128, 1, 64)])
+def test_pair_split_reconstruct_variant(sfb, J, D, P, B):
+    """Variant 11 (tiles of 3 to 5 row blocks x 64 columns, the four wavefronts split the two column blocks and
+    every stage's pairs; D % 64 == 0, J % 4 == 0, N % 32 == 0): each of the three tile heights (J = 600, 388,
+    1000, 440: five row blocks; 256, 352: four; 96, 68: three), ragged last row tile and ragged last row block,
+    one to many stages (N = 32 ... 1024), a single tile."""
+    wl = workloads.make("mlr_medium", seed=11, J=J, D=D, P=P, B=B, steps=3, pool=2)
+    run_chain(wl, 3, TOL32, plan=dict(recon_variant=11))
+
+
+def test_pair_split_variant_is_what_the_plan_picks_for_600_rows_and_falls_back_when_it_must(sfb):
     import paper_1511_08486_amd as m
     ctx = m.Sfb("dml", 600, 4096, 8, 128, device="cuda:0")
-    assert ctx.plan_info()["recon_grid"] == 10 * 64          # 64 x 64 tiles
+    assert ctx.plan_info()["recon_grid"] == 4 * 64           # four row tiles of five row blocks x 64-column tiles
     ctx.close()
+    # shapes the kernel does not take run the single-block kernel or, failing that too, the others: J = 40
+    # (two row blocks), D % 64 != 0, N % 32 != 0
+    wl = workloads.make("mlr_medium", seed=12, J=40, D=128, P=2, B=32, steps=2, pool=2)
+    run_chain(wl, 2, TOL32, plan=dict(recon_variant=11))
+    wl = workloads.make("mlr_medium", seed=13, J=600, D=200, P=3, B=20, steps=2, pool=2)
+    run_chain(wl, 2, TOL32, plan=dict(recon_variant=11))
+
+
+def test_single_block_variant_falls_back_when_it_must(sfb):
+    import paper_1511_08486_amd as m
     ctx = m.Sfb("mlr", 1000, 4096, 8, 64, device="cuda:0")
     assert ctx.plan_info()["recon_grid"] == 256              # a tie in the block count keeps the 128 x 128 tiles
     ctx.close()

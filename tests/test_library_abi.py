@@ -224,11 +224,12 @@ def test_prox_validates_before_launching(lib):
 
 def test_launch_plans_of_the_benchmark_shapes(lib):
     """The planner is host code: tile counts for the five benchmark shapes (no GPU needed).
-    mlr_medium: 128x128 tiles, one per compute unit; dml: 600 rows take the 64x64 single-block tiles;
+    mlr_medium: 128x128 tiles, one per compute unit; dml: 600 rows take four row tiles of five row blocks x 64
+    column tiles, one workgroup per compute unit;
     l2svm: 128x128 tiles, four per compute unit; mlr_large: 256x128 bf16 tiles."""
     import paper_1511_08486_amd as sfb
     want = {("mlr", 10, 100, 4, 16, "f32"): 1, ("mlr", 1000, 4096, 8, 64, "f32"): 256,
-            ("dml", 600, 4096, 8, 128, "f32"): 640, ("l2svm", 2000, 8192, 16, 64, "f32"): 1024}
+            ("dml", 600, 4096, 8, 128, "f32"): 256, ("l2svm", 2000, 8192, 16, 64, "f32"): 1024}
     for (model, J, D, P, B, dt), grid in want.items():
         ctx = C.c_void_p()
         assert lib.sfb_create(C.byref(ctx), sfb.binding._MODELS[model], J, D, P, B, sfb.binding._DTYPES[dt], None) == 0
@@ -237,9 +238,9 @@ def test_launch_plans_of_the_benchmark_shapes(lib):
         assert r.value == grid, (model, J, D, r.value)
         assert k.value >= 1 and g.value >= 1
         # every variant of the table can be selected; one past the end cannot
-        for v in range(11):
+        for v in range(12):
             assert lib.sfb_set_plan(ctx, 0, 0, 0, v, -1) == 0
-        assert lib.sfb_set_plan(ctx, 0, 0, 0, 11, -1) == -1
+        assert lib.sfb_set_plan(ctx, 0, 0, 0, 12, -1) == -1
         lib.sfb_destroy(ctx)
 
 
