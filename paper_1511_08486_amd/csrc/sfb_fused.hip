@@ -241,13 +241,10 @@ __global__ __launch_bounds__(kFuThreads) void update_score_kernel(
         {
             unsigned char* mine = fu_lds + X_OFF + rb * 4096 + kh * 2048;
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int e0 = kh == 0 ? 8 + 4 * j : 4 * j;
+            for (int j = 0; j < 2; ++j)      // kh = 0 hands over entries 8..15, kh = 1 entries 0..7 (a select, no indexing)
                 *reinterpret_cast<f32x4*>(mine + j * 1024 + lane * 16) =
                     kh == 0 ? f32x4{acc[8 + 4 * j], acc[9 + 4 * j], acc[10 + 4 * j], acc[11 + 4 * j]}
                             : f32x4{acc[4 * j], acc[1 + 4 * j], acc[2 + 4 * j], acc[3 + 4 * j]};
-                (void)e0;
-            }
         }
         // ---- partial sums exchanged, the W tile has landed; the v^T stage is free again ----
         fu_wait_vm(issued - mark_w);
