@@ -312,17 +312,20 @@ __global__ __launch_bounds__(kFuThreads) void update_score_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// Received factors -> the operands of phase 1:
+// Received factors -> the operands of phase 1, and the next batch's features -> the A operand of phase 2:
 //   UT[j][n] = bf16(alpha * U[n][j])                       row-major, n contiguous
 //   VTp: v^T tile by tile (32 columns of W x N pairs), each tile in the swizzled LDS order of the kernel
 //        above: element (column r of the tile, pair k) at item ((k/64)*32 + r)*8 + ((k/8 % 8) ^ key8(r))
-// Rows of dead workers are written as zeros.  64 x 64 tiles through LDS; blocks [0, n_jblk) of a
-// row of blocks do U, the rest V.
+//   AnP: the next features tile by tile (N samples x 32 columns), item p of sample n at n*4 + (p ^ key4(n))
+//   V  : takes the next features (v_i = a_i, Section 2.1) once its old contents have been packed
+// Rows of dead workers go into UT and VTp as zeros.  64 x 64 tiles through LDS; blocks [0, n_jblk) of a row
+// of blocks do U, the rest V.  A V block is the only one that touches its 64 samples x 64 columns of V: it
+// reads them (v_t), and after its barrier, when every one of those reads has returned, overwrites them.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void fused_pack_kernel(
-    const float* __restrict__ U, int64_t ldu, const bf16_t* __restrict__ V, int64_t ldv, bf16_t* __restrict__ UT,
-    bf16_t* __restrict__ VTp, int N, int J, int D, int B, float alpha, uint64_t live_mask, bool use_mask, int n_jblk,
-    int n_dblk) {
+    const float* __restrict__ U, int64_t ldu, bf16_t* __restrict__ V, int64_t ldv, const bf16_t* __restrict__ A,
+    int64_t lda, bf16_t* __restrict__ UT, bf16_t* __restrict__ VTp, bf16_t* __restrict__ AnP, int N, int J, int D, int B,
+    float alpha, uint64_t live_mask, bool use_mask, int n_jblk, int n_dblk) {
     __shared__ __attribute__((aligned(16))) bf16_t tile[64][72];   // [column of the source][n], 144-byte rows
     const int tid = threadIdx.x;
     const int n_cblk = n_jblk + n_dblk;
@@ -330,6 +333,15 @@ __global__ __launch_bounds__(256) void fused_pack_kernel(
     const bool is_u = cb < n_jblk;
     const int c0 = (is_u ? cb : cb - n_jblk) * 64, k0 = kb * 64;
     const int ncols = is_u ? J : D;
+    // the next features of this block's samples and columns: two 16-byte items per thread, requested first
+    u32x4 nxt[2];
+    if (!is_u) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int idx = tid + 256 * i, n = k0 + idx / 8, c = c0 + 8 * (idx % 8);
+            nxt[i] = c < D ? *reinterpret_cast<const u32x4*>(A + (int64_t)n * lda + c) : u32x4{0, 0, 0, 0};
+        }
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int n = k0 + (tid >> 4) + 16 * i, c = c0 + (tid & 15) * 4;
@@ -358,17 +370,16 @@ __global__ __launch_bounds__(256) void fused_pack_kernel(
             *reinterpret_cast<u32x4*>(VTp + (int64_t)t * (32 * N) + slot * 8) = item;
         }
     }
-}
-
-// Next batch's features -> the A operand of phase 2, tile by tile (N samples x 32 columns), each tile in the
-// kernel's swizzled LDS order (item p of sample n at n*4 + (p ^ key4(n))), and -> V (v_i = a_i, Section 2.1).
-__global__ __launch_bounds__(256) void fused_stage_next_kernel(const bf16_t* __restrict__ A, int64_t lda,
-                                                               bf16_t* __restrict__ AnP, bf16_t* __restrict__ Vout,
-                                                               int64_t ldv, int N, int n_nblk) {
-    const int t = blockIdx.x / n_nblk, n = (blockIdx.x % n_nblk) * 64 + (threadIdx.x >> 2), p = threadIdx.x & 3;
-    const u32x4 item = *reinterpret_cast<const u32x4*>(A + (int64_t)n * lda + t * kFuCols + 8 * p);
-    *reinterpret_cast<u32x4*>(AnP + (int64_t)t * (32 * N) + ((int64_t)n * 4 + (p ^ fu_key4(n))) * 8) = item;
-    *reinterpret_cast<u32x4*>(Vout + (int64_t)n * ldv + t * kFuCols + 8 * p) = item;
+    if (!is_u) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int idx = tid + 256 * i, n = k0 + idx / 8, c = c0 + 8 * (idx % 8);
+            if (c >= D) continue;
+            const int t = c / kFuCols, p = (c % kFuCols) / 8;
+            *reinterpret_cast<u32x4*>(AnP + (int64_t)t * (32 * N) + ((int64_t)n * 4 + (p ^ fu_key4(n))) * 8) = nxt[i];
+            *reinterpret_cast<u32x4*>(V + (int64_t)n * ldv + c) = nxt[i];
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -427,16 +438,11 @@ hipError_t launch_fused(const FusedArgs& a, const FusedPlan& p, void* ws_factors
     bf16_t* VTp = (bf16_t*)((char*)ws_factors + up((size_t)a.J * a.N * 2));
     bf16_t* AnP = (bf16_t*)ws_next;
     const int n_jblk = (a.J + 63) / 64, n_dblk = a.D / 64 + (a.D % 64 ? 1 : 0), n_kblk = a.N / 64;
-    // plain launches: an armed pair of timing events belongs to the fused kernel below
-    hipLaunchKernelGGL(fused_pack_kernel, dim3((n_jblk + n_dblk) * n_kblk), dim3(256), 0, s, a.u, a.ldu,
-                       (const bf16_t*)a.v, a.ldv, UT, VTp, a.N, a.J, a.D, a.B, a.alpha, a.live_mask, a.use_mask, n_jblk,
-                       n_dblk);
+    // a plain launch: an armed pair of timing events belongs to the fused kernel below
+    hipLaunchKernelGGL(fused_pack_kernel, dim3((n_jblk + n_dblk) * n_kblk), dim3(256), 0, s, a.u, a.ldu, (bf16_t*)a.v, a.ldv,
+                       (const bf16_t*)a.a_next, a.lda, UT, VTp, AnP, a.N, a.J, a.D, a.B, a.alpha, a.live_mask, a.use_mask,
+                       n_jblk, n_dblk);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    // v_t has been packed: V may now take the next batch's features
-    hipLaunchKernelGGL(fused_stage_next_kernel, dim3((a.D / kFuCols) * n_kblk), dim3(256), 0, s, (const bf16_t*)a.a_next,
-                       a.lda, AnP, (bf16_t*)a.v, a.ldv, a.N, n_kblk);
-    e = hipGetLastError();
     if (e != hipSuccess) return e;
     switch (a.N) {
         case 128: return launch_update_score<1>(a, p, UT, VTp, AnP, s);
