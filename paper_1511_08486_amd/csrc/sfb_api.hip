@@ -217,7 +217,7 @@ sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t
             hipError_t e = launch_csr_densify(d, c->stream);
             if (e != hipSuccess) return hip_fail(c, e);
         }
-        if (c->sparse_forward && csr_scores_ok((int)c->D) && b->nnz < (int64_t)INT32_MAX) {
+        if (c->sparse_forward && csr_scores_ok((int)c->D) && b->nnz <= (1LL << 30) - 1024) {
             // scores from the stored entries only: 2*nnz*J flops instead of 2*N*J*D
             Timed t(c, 0);
             hipError_t e = launch_csr_scores(d, W, ldw, (float*)c->ws, ldz, (int)c->J, c->stream);

@@ -134,39 +134,61 @@ __global__ __launch_bounds__(kSpThreads) void csr_scores_kernel(
     }
     __syncthreads();
 
-    // Everything below is 32-bit index arithmetic on purpose (the host checks nnz < 2^31): the
-    // kernel is bound by the number of vector instructions per stored entry, not by memory.
-    const int last = (int)nnz - 1;
+    // The kernel is bound by the number of vector instructions per stored entry, not by memory, so the
+    // per-entry bookkeeping is kept off the vector unit:
+    //  * col and val are read through buffer descriptors: the address is (one 32-bit byte offset per sample
+    //    and lane) + an immediate per slab, and an offset beyond the array returns 0 by hardware, so there
+    //    is no 64-bit address arithmetic and no clamp (the host checks nnz <= 2^30 - 1024: the byte range of
+    //    a descriptor and the offsets are 32-bit);
+    //  * the wavefront number is made scalar, so row pointers are scalar loads and their clamps scalar
+    //    arithmetic;
+    //  * a lane past the end of its row gets value 0 (one compare + one select per slab); its column is
+    //    whatever the array holds there (an entry of a later row, or 0 past the end): a valid place in the
+    //    parked rows, multiplied by zero.
+    const __amdgpu_buffer_rsrc_t col_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)col, (short)0, (int)((uint32_t)nnz * 4u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)val, (short)0, (int)((uint32_t)nnz * 4u), 0x00020000);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t dmax = (uint32_t)(D - 1);
     // row pointers of a batch of consecutive samples (clamped into [0, nnz]: a row pointer
     // outside is a caller error and must not carry an access out of the arrays)
     auto load_ptrs = [&](int n, int (&p)[kSpBatch + 1]) {
 #pragma unroll
-        for (int s = 0; s <= kSpBatch; ++s) p[s] = min(max(rowptr[min(n + s, n_rows)], 0), last + 1);
+        for (int s = 0; s <= kSpBatch; ++s) p[s] = min(max(rowptr[min(n + s, n_rows)], 0), (int)nnz);
     };
-    int ptr[kSpBatch + 1], next_ptr[kSpBatch + 1];
-    int n = wave * kSpBatch;
-    if (n < n_rows) load_ptrs(n, ptr);
-    for (; n < n_rows; n += NW * kSpBatch) {
-        const int n_next = n + NW * kSpBatch;
-        if (n_next < n_rows) load_ptrs(n_next, next_ptr);   // one batch ahead
-        // issue every load of the batch's first slabs before using any of them: addresses are
-        // always valid (clamped) and a select zeroes what lies outside the row, so no branch
-        // sits between the loads and all of them are in flight together
-        uint32_t cc[kSpBatch][kSpPre];
-        float vv[kSpBatch][kSpPre];
+    // the first slabs of a batch: every load is issued before any is used, no branch in between
+    auto load_entries = [&](const int (&p)[kSpBatch + 1], uint32_t (&c)[kSpBatch][kSpPre], float (&v)[kSpBatch][kSpPre]) {
 #pragma unroll
-        for (int s = 0; s < kSpBatch; ++s)
+        for (int s = 0; s < kSpBatch; ++s) {
+            const int off = (int)((uint32_t)(p[s] + lane) * 4u);   // byte offset of this lane's entry of slab 0
+            const int left = p[s + 1] - p[s] - lane;         // > 64 * it: the lane's entry of slab it belongs to the row
 #pragma unroll
             for (int it = 0; it < kSpPre; ++it) {
-                const int e = ptr[s] + it * 64 + lane;
-                const int ec = min(e, last);
-                const uint32_t cl = (uint32_t)col[ec];
-                const float vl = val[ec];
-                const bool in = e < ptr[s + 1];
-                vv[s][it] = in ? vl : 0.f;
-                cc[s][it] = in ? min(cl, dmax) : 0u;       // a column outside [0, D) is a caller error: stay inside the LDS tile
+                const uint32_t cl = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(col_rsrc, off + it * 256, 0, 0);
+                const float vl = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(val_rsrc, off + it * 256, 0, 0));
+                v[s][it] = left > it * 64 ? vl : 0.f;
+                c[s][it] = min(cl, dmax);                    // a column outside [0, D) is a caller error: stay inside the LDS tile
             }
+        }
+    };
+    // Three batches are in flight per wavefront: the one being multiplied (its entries were requested a
+    // round ago), the next (row pointers here, entries requested now) and the one after (row pointers
+    // requested now), so that the trips to L2 for the CSR arrays run under the LDS gathers of the round
+    // before instead of in front of every round.
+    int ptr[kSpBatch + 1], next_ptr[kSpBatch + 1], after_ptr[kSpBatch + 1];
+    uint32_t cc0[kSpBatch][kSpPre], cc1[kSpBatch][kSpPre];
+    float vv0[kSpBatch][kSpPre], vv1[kSpBatch][kSpPre];
+    constexpr int STRIDE = NW * kSpBatch;
+    int n = wave_s * kSpBatch;
+    if (n < n_rows) {
+        load_ptrs(n, ptr);
+        load_entries(ptr, cc0, vv0);
+    }
+    if (n + STRIDE < n_rows) load_ptrs(n + STRIDE, next_ptr);
+    // one round: request the next batch's entries into (ncc, nvv), multiply the batch held in (cc, vv)
+    auto round = [&](uint32_t (&cc)[kSpBatch][kSpPre], float (&vv)[kSpBatch][kSpPre], uint32_t (&ncc)[kSpBatch][kSpPre],
+                     float (&nvv)[kSpBatch][kSpPre]) {
+        if (n + 2 * STRIDE < n_rows) load_ptrs(n + 2 * STRIDE, after_ptr);
+        if (n + STRIDE < n_rows) load_entries(next_ptr, ncc, nvv);
         float acc[kSpBatch * kSpRows];                      // [sample][class]
 #pragma unroll
         for (int s = 0; s < kSpBatch; ++s) {
@@ -175,11 +197,10 @@ __global__ __launch_bounds__(kSpThreads) void csr_scores_kernel(
             for (int it = 0; it < kSpPre; ++it) a += vv[s][it] * *reinterpret_cast<const f32x4*>(&wcols[cc[s][it] * 4]);
             // rows longer than the prefetched slabs (uniform trip count per wavefront)
             for (int e0 = ptr[s] + kSpPre * 64; e0 < ptr[s + 1]; e0 += 64) {
-                const int e = e0 + lane;
-                const int ec = min(e, last);
-                const uint32_t cl = min((uint32_t)col[ec], dmax);
-                const float vl = e < ptr[s + 1] ? val[ec] : 0.f;
-                a += vl * *reinterpret_cast<const f32x4*>(&wcols[cl * 4]);
+                const int off = (int)((uint32_t)(e0 + lane) * 4u);
+                const uint32_t cl = min((uint32_t)__builtin_amdgcn_raw_buffer_load_b32(col_rsrc, off, 0, 0), dmax);
+                const float vl = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(val_rsrc, off, 0, 0));
+                a += (e0 + lane < ptr[s + 1] ? vl : 0.f) * *reinterpret_cast<const f32x4*>(&wcols[cl * 4]);
             }
 #pragma unroll
             for (int r = 0; r < kSpRows; ++r) acc[s * kSpRows + r] = a[r];
@@ -187,25 +208,27 @@ __global__ __launch_bounds__(kSpThreads) void csr_scores_kernel(
         // Halving butterfly over all 16 sums of the batch at once: at every exchange a lane
         // gives away half of what it still holds and adds what it receives to the other half,
         // 8 + 4 + 2 + 1 exchanges; then two more for the last factor four.  Lane l ends up with
-        // value index (l >> 2) & 15 summed over all 64 lanes (17 exchanges instead of 96).
+        // value index (l >> 2) & 15 summed over all 64 lanes (17 exchanges instead of 96).  The exchanges
+        // over 32 and 16 lanes are one swap instruction each: v_permlane32_swap trades the upper half of
+        // its first operand for the lower half of its second (v_permlane16_swap: the odd rows of 16 lanes
+        // for the even rows), after which "kept + received" is the sum of the two registers.
         static_assert(kSpBatch * kSpRows == 16, "butterfly below is written for 16 values");
+        // (written as instructions: the compiler's own form of these two returned one register twice in the
+        // sums below; the waits before and after cover the instruction's issue rules for operands that a
+        // vector instruction has just written or is about to read)
         float v8[8], v4[4], v2[2], v1;
-        {
-            const bool hi = lane & 32;
+        asm volatile("s_nop 1");
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const float give = hi ? acc[k] : acc[k + 8], keep = hi ? acc[k + 8] : acc[k];
-                v8[k] = keep + __shfl_xor(give, 32, 64);            // lanes < 32 keep values 0..7, the rest 8..15
-            }
-        }
-        {
-            const bool hi = lane & 16;
+        for (int k = 0; k < 8; ++k) asm volatile("v_permlane32_swap_b32 %0, %1" : "+v"(acc[k]), "+v"(acc[k + 8]));
+        asm volatile("s_nop 1");
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const float give = hi ? v8[k] : v8[k + 4], keep = hi ? v8[k + 4] : v8[k];
-                v4[k] = keep + __shfl_xor(give, 16, 64);
-            }
-        }
+        for (int k = 0; k < 8; ++k) v8[k] = acc[k] + acc[k + 8];       // lanes < 32 now hold values 0..7, the rest 8..15
+        asm volatile("s_nop 1");
+#pragma unroll
+        for (int k = 0; k < 4; ++k) asm volatile("v_permlane16_swap_b32 %0, %1" : "+v"(v8[k]), "+v"(v8[k + 4]));
+        asm volatile("s_nop 1");
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v4[k] = v8[k] + v8[k + 4];         // bit 4 of the lane clear: value k, set: k + 4
         {
             const bool hi = lane & 8;
 #pragma unroll
@@ -227,12 +250,21 @@ __global__ __launch_bounds__(kSpThreads) void csr_scores_kernel(
             if ((lane & 3) == 0 && n + sm < n_rows && j0 + r < J) Z[(int64_t)(n + sm) * ldz + j0 + r] = v1;
         }
 #pragma unroll
-        for (int s = 0; s <= kSpBatch; ++s) ptr[s] = next_ptr[s];
+        for (int s = 0; s <= kSpBatch; ++s) {
+            ptr[s] = next_ptr[s];
+            next_ptr[s] = after_ptr[s];
+        }
+        n += STRIDE;
+    };
+    // the two register sets trade places every round (no copies)
+    while (n < n_rows) {
+        round(cc0, vv0, cc1, vv1);
+        if (n < n_rows) round(cc1, vv1, cc0, vv0);
     }
 }
 
 bool csr_scores_ok(int D) { return (size_t)D * kSpRows * sizeof(float) <= 160 * 1024 - 1024; }
-// (the caller also needs nnz < 2^31: the kernel indexes the CSR arrays with 32-bit integers)
+// (the caller also needs nnz <= 2^30 - 1024: the kernel reads the CSR arrays through 32-bit byte offsets)
 
 hipError_t launch_csr_scores(const DensifyArgs& a, const float* W, int64_t ldw, float* Z, int64_t ldz, int J,
                              hipStream_t s) {
