@@ -176,8 +176,9 @@ SFB_API sfb_status sfb_step(sfb_ctx *ctx, float *W, int64_t ldw, const sfb_batch
  * (P*B in {128, 256, 512}, D a multiple of 32, J*ldw < 2^31, 16-byte aligned operands) the update and
  * the next scores run in ONE kernel that reads and writes every tile of W once; otherwise the call runs
  * sfb_reconstruct_apply and sfb_compute_factors one after the other (same results as sfb_step).
- * `active` masks the workers of the PENDING factors.  Needs the registered workspace (query
- * sfb_workspace_bytes).  Errors as sfb_step; nothing is launched if an argument is refused.
+ * `active` masks the workers of the PENDING factors.  The next batch's features must not overlap V
+ * (V is read as v_t and overwritten with the next features piece by piece).  Needs the registered
+ * workspace (query sfb_workspace_bytes).  Errors as sfb_step; nothing is launched if an argument is refused.
  * sfb_pipeline_info: whether the fused kernel is what the context would run (0 / 1), its grid and
  * its number of column slices (0 when not fused); any pointer may be NULL.
  */
