@@ -145,6 +145,23 @@ def test_l2svm_ragged_and_empty_rows(sfb, dense_scores):
     run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else None)
 
 
+def test_l2svm_rows_longer_than_the_score_kernel_prefetches(sfb):
+    """The score kernel requests the first 3 x 64 stored entries of a row up front and loops over the rest: rows of
+    451 entries (eight slabs), and of 193, 192, 191, 129, 128, 65, 64, 63, 1 and 0 entries around the slab
+    boundaries, the last row ending exactly at the end of the arrays."""
+    wl = workloads.make("l2svm", seed=31, J=37, D=2048, P=3, B=7, steps=2, density=0.22)
+    lengths = [451, 193, 192, 191, 129, 128, 65, 64, 63, 1, 0]
+    for b in wl.batches:
+        per = b["rowptr"][1]
+        assert per == 451
+        counts = np.array([lengths[r % len(lengths)] for r in range(wl.N)])
+        counts[-1] = 451
+        keep = np.concatenate([np.arange(r * per, r * per + counts[r]) for r in range(wl.N)]).astype(np.int64)
+        b["col"], b["val"] = b["col"][keep], b["val"][keep]
+        b["rowptr"] = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    run_chain(wl, 2, TOL32)
+
+
 def test_l2svm_dense_score_fallback_full_size(sfb):
     wl = workloads.make("l2svm", pool=2)
     run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3))
