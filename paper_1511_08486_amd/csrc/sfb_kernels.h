@@ -158,7 +158,7 @@ hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_
 bool reconstruct_small_ok(const ReconArgs& a);
 bool reconstruct_small_wins(int64_t J, int64_t D, int big_bm, int big_waves);
 hipError_t launch_reconstruct_small(const ReconArgs& a, hipStream_t s);
-// (96..160) x 64 tiles whose four wavefronts split the two column blocks AND every stage's pairs
+// (96..160) x 64 tiles whose eight wavefronts split the two column blocks, every stage's pairs and the stages
 // (sfb_reconstruct_ksplit.hip): for shapes where even single blocks leave the busiest SIMD well above the average
 bool reconstruct_ksplit_ok(const ReconArgs& a);
 bool reconstruct_ksplit_wins(int64_t J, int64_t D, int64_t other_blocks);

@@ -551,7 +551,7 @@ static const ReconVariant kReconVariants[] = {
     {1, 2, 1, true},   // 8: 64 x 128, 2 wavefronts, LDS-DMA staging (falls back to 1)
     {1, 2, 1, true},   // 9: 64 x 64, 4 wavefronts of one 32 x 32 block each, LDS-DMA staging (falls back to 8)
     {1, 4, 1, true},   // 10: as 7 with 16-pair stages and a register budget for two workgroups per compute unit
-    {1, 2, 1, true},   // 11: (96..160) x 64, 4 wavefronts = 2 column blocks x 2 halves of every stage's pairs (falls back to 9)
+    {1, 2, 1, true},   // 11: (96..160) x 64, 8 wavefronts = 2 column blocks x 2 halves of every stage's pairs x 2 groups taking the stages in turn (falls back to 9)
 };
 constexpr int kSmallVariant = 9, kKsplitVariant = 11;
 constexpr int kNumReconVariants = sizeof(kReconVariants) / sizeof(kReconVariants[0]);

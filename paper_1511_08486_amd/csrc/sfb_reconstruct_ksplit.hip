@@ -1,26 +1,36 @@
 // Reconstruction + update (Section 3, Section 2.1), evenly divided form:
 //     W[j][d] <- W[j][d] + alpha * sum_n U[n][j] * V[n][d]
-// with tiles of 32*RB rows x 64 columns of W and four wavefronts that split BOTH the tile's
-// two column blocks and every stage's factor pairs.
+// with tiles of 32*RB rows x 64 columns of W and eight wavefronts that split the tile's two
+// column blocks, every chunk's factor pairs, and the chunks themselves.
 //
 // Why a third tile shape.  A launch is as slow as its busiest SIMD.  The unit the other kernels
 // hand out is a whole 32 x 32 block of W carried through all N pairs: J = 600, D = 4096 is
 // 19 x 128 = 2432 blocks for 1024 SIMDs, 2.4 each on average but 3 on the busiest even with
 // single-block wavefronts (and a lone wavefront in the last round hides none of its waits: 3.5
 // block times measured).  Here a wavefront carries RB blocks (one column block of the tile, all
-// its row blocks) through HALF of the pairs, its partner the other half; the two exchange partial
-// sums through LDS once, at the end, and each finishes half of every block.  J = 600 becomes four
-// row tiles of five row blocks x 64 column tiles = 256 workgroups, one per compute unit, and
-// every SIMD multiplies exactly 5 blocks x N/2 pairs = 2.5 block times, 95 % of it on rows that
-// exist.  The B fragment (v) of a step feeds RB matrix instructions, and four of the row blocks
-// share one 16-byte LDS read (rows interleaved by four, as the columns are in the large kernel).
+// its row blocks) through a QUARTER of the pairs; the four wavefronts that share the blocks
+// exchange partial sums through LDS once, at the end, and each finishes a quarter of every block.
+// J = 600 becomes four row tiles of five row blocks x 64 column tiles = 256 workgroups, one per
+// compute unit, and every SIMD multiplies exactly 5 blocks x N/2 pairs = 2.5 block times, 95 % of
+// it on rows that exist.  The B fragment (v) of a step feeds RB matrix instructions, and four of the
+// row blocks share one 16-byte LDS read (rows interleaved by four, as the columns are in the large
+// kernel).
 //
-// Staging is the LDS-DMA ring of the other kernels: per stage 32 pairs of u [k][32*RB] and of
-// v [k][64] go from L2 straight into LDS, four stages, completion counted by hand with the
-// in-order vector-memory counter; the W entries a wavefront finishes are requested after the
-// first stage and consumed in the epilogue, where alpha and the entrywise proximal operator are
-// applied.  Sums are formed as (first half of every stage's pairs) + (second half), then added
-// to W: one fixed order, results do not depend on timing.
+// The eight wavefronts are two per SIMD, in two groups of four that take the chunks of 32 pairs in
+// turn (group 0 the even chunks, group 1 the odd ones); inside a group: 2 column blocks x 2 halves of
+// the chunk's pairs.  With one wavefront per SIMD every hand-over to the next chunk (wait for the
+// copies, barrier, issue the next copies, first LDS reads) is time the matrix pipe stands still (a
+// four-wavefront form of this kernel lost 5.3 of its 42.6 ns per pair that way); here the other
+// group's wavefront on the same SIMD is in the middle of its own chunk at that moment and keeps the
+// pipe busy.  Barrier number c is the hand-over to chunk c: the group that owns chunk c reaches it
+// between two chunks, the other group in the middle of chunk c - 1 (20 of its 40 matrix instructions
+// issued); every wavefront executes every barrier exactly once.  A group stages its own chunks by
+// LDS-DMA (32 pairs of u [k][32*RB] and of v [k][64] straight from L2, a ring of four stages, two per
+// group, completion counted by hand with the in-order vector-memory counter) and only it reads them,
+// so a chunk's stage is free again as soon as the group has passed its next hand-over.  The W entries
+// a wavefront finishes are requested during its first chunk and consumed in the epilogue, where alpha
+// and the entrywise proximal operator are applied.  Four partial sums per entry (2 halves x 2 groups)
+// are added in one fixed order (quarter owners 0, 1, 2, 3), then to W: results do not depend on timing.
 #include <type_traits>
 
 #include "sfb_device.h"
@@ -28,59 +38,49 @@
 
 namespace sfb {
 
-constexpr int kRksBN = 64, kRksBK = 32, kRksStages = 4, kRksThreads = 256;
+constexpr int kRksBN = 64, kRksBK = 32;
 
 template <int RB>
-__global__ __launch_bounds__(kRksThreads) void reconstruct_apply_ksplit_kernel(
+__global__ __launch_bounds__(512) void reconstruct_apply_ksplit_kernel(
     float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const float* __restrict__ V,
     int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total, int prox_kind, float prox_a) {
-    constexpr int BM = 32 * RB, BN = kRksBN, BK = kRksBK, NST = kRksStages, THREADS = kRksThreads;
-    constexpr int U_LD = BK * BM / 4 / THREADS, V_LD = BK * BN / 4 / THREADS;      // 16-byte DMAs per thread and stage
+    constexpr int BM = 32 * RB, BN = kRksBN, BK = kRksBK, GT = 256;   // GT: threads of a group; ring of four stages
+    constexpr int U_LD = BK * BM / 4 / GT, V_LD = BK * BN / 4 / GT;               // 16-byte DMAs per thread and chunk
     constexpr int DMAS = U_LD + V_LD;
     constexpr int STAGE_FLOATS = BK * (BM + BN);
-    constexpr int NQD = RB / 4;                  // groups of four row blocks read with one 16-byte LDS read (rows interleaved)
-    constexpr int NS = RB - 4 * NQD;             // remaining row blocks: 32 consecutive rows each
-    constexpr int W_LOADS = RB * 8;              // a wavefront finishes half of each of its RB blocks
+    constexpr int NQD = RB / 4, NS = RB - 4 * NQD;
+    constexpr int W_LOADS = RB * 4;              // a wavefront finishes a quarter of each of its RB blocks
     static_assert(U_LD == RB && V_LD == 2, "tile / thread count mismatch");
-    static_assert(NST == 4, "ring depth");
     static_assert(DMAS + W_LOADS <= 63, "wait count encoding");
-    static_assert(4 * RB * 2 * 1024 <= NST * STAGE_FLOATS * 4, "the exchange area reuses the stage ring");
-    extern __shared__ __attribute__((aligned(16))) float rks_lds[];      // NST * STAGE_FLOATS
+    extern __shared__ __attribute__((aligned(16))) float rks_lds[];   // max(ring, exchange area): see the launcher
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const int wc = wave & 1, kh = wave >> 1;                // column block of the tile, half of every stage's pairs
+    const int g = wave >> 2, gw = wave & 3, gtid = tid & (GT - 1);
+    const int wc = gw & 1, kh = gw >> 1;
     const int id = xcd_contiguous_id(blockIdx.x, total);
     const int jb = id % n_jb, db = id / n_jb;
     const int j0 = jb * BM, d0 = db * BN;
 
-    // source of DMA i of a stage: item idx = tid + i * THREADS of the [k][BM] (resp. [k][64]) tile in row-major
-    // order of 16-byte items.  Columns of U beyond J are clamped (host: J % 4 == 0, J >= 4): they feed rows
-    // of W that are never stored.
     const float* pu[U_LD];
     const float* pv[V_LD];
 #pragma unroll
     for (int i = 0; i < U_LD; ++i) {
-        const int idx = tid + i * THREADS;
+        const int idx = gtid + i * GT;
         pu[i] = U + (int64_t)(idx / (BM / 4)) * ldu + min(j0 + (idx % (BM / 4)) * 4, J - 4);
     }
 #pragma unroll
     for (int i = 0; i < V_LD; ++i) {
-        const int idx = tid + i * THREADS;
+        const int idx = gtid + i * GT;
         pv[i] = V + (int64_t)(idx / (BN / 4)) * ldv + d0 + (idx % (BN / 4)) * 4;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)rks_lds;
     const int64_t ustep = (int64_t)BK * ldu, vstep = (int64_t)BK * ldv;
-    auto issue = [&](int chunk, int st) {
-        const uint32_t ubase = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(st * STAGE_FLOATS + wave * 64 * 4) * 4u);
-        const uint32_t vbase = ubase + (uint32_t)(BK * BM) * 4u;
-#pragma unroll
-        for (int i = 0; i < U_LD; ++i) lds_dma16(pu[i] + chunk * ustep, ubase + (uint32_t)(i * THREADS * 16));
-#pragma unroll
-        for (int i = 0; i < V_LD; ++i) lds_dma16(pv[i] + chunk * vstep, vbase + (uint32_t)(i * THREADS * 16));
+    auto issue_one = [&](int chunk, int i) {
+        const uint32_t ubase = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)((chunk & 3) * STAGE_FLOATS + gw * 64 * 4) * 4u);
+        if (i < U_LD) lds_dma16(pu[i] + chunk * ustep, ubase + (uint32_t)(i * GT * 16));
+        else lds_dma16(pv[i - U_LD] + chunk * vstep, ubase + (uint32_t)(BK * BM) * 4u + (uint32_t)((i - U_LD) * GT * 16));
     };
-
-    // Row of the tile that accumulator entry m (0..31, the MFMA row index) of block b stands for.
     auto tile_row = [](int b, int m) { return b < 4 * NQD ? 128 * (b / 4) + 4 * m + (b % 4) : 128 * NQD + 32 * (b - 4 * NQD) + m; };
 
     f32x16 acc[RB];
@@ -89,14 +89,10 @@ __global__ __launch_bounds__(kRksThreads) void reconstruct_apply_ksplit_kernel(
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
 
-    // MFMA k-step s (0..7) of this wavefront's half covers pairs 16 kh + 2 s and + 1 of the stage: lanes 0-31
-    // carry the first (row / column l32), lanes 32-63 the second.  The operand words of four k-steps form one
-    // set of fragments; a stage is two sets.
     struct Frags {
         f32x4 aq[4][NQD > 0 ? NQD : 1];
         float as[4][NS > 0 ? NS : 1], bv[4];
     };
-    // k-step s of half h of a stage
     auto load_step = [&](int st, int h, int s, Frags& f) {
         const float* us = &rks_lds[st * STAGE_FLOATS + (16 * kh + 8 * h + half) * BM];
         const float* vs = &rks_lds[st * STAGE_FLOATS + BK * BM + (16 * kh + 8 * h + half) * BN + wc * 32 + l32];
@@ -106,13 +102,6 @@ __global__ __launch_bounds__(kRksThreads) void reconstruct_apply_ksplit_kernel(
         for (int r = 0; r < NS; ++r) f.as[s][r] = us[2 * s * BM + 128 * NQD + 32 * r + l32];
         f.bv[s] = vs[2 * s * BN];
     };
-    auto load_frags = [&](int st, int h, Frags& f) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) load_step(st, h, s, f);
-    };
-    // The matrix instructions of one set; between(s) runs after those of k-step s: whatever else has to be
-    // issued (LDS reads of a later set, copies of a later chunk) goes there, one piece per k-step, so that it
-    // is issued in the shadow of the matrix pipe instead of in one lump between two sets.
     auto multiply = [&](const Frags& f, auto between) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
@@ -130,101 +119,102 @@ __global__ __launch_bounds__(kRksThreads) void reconstruct_apply_ksplit_kernel(
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    // copy instruction i (0 .. DMAS - 1) of a chunk
-    auto issue_one = [&](int chunk, int st, int i) {
-        const uint32_t ubase = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(st * STAGE_FLOATS + wave * 64 * 4) * 4u);
-        if (i < U_LD) lds_dma16(pu[i] + chunk * ustep, ubase + (uint32_t)(i * THREADS * 16));
-        else lds_dma16(pv[i - U_LD] + chunk * vstep, ubase + (uint32_t)(BK * BM) * 4u + (uint32_t)((i - U_LD) * THREADS * 16));
-    };
-    auto wait_allowing = [&](int allowed) {      // at most `allowed` younger operations may still be outstanding
-        if (allowed >= DMAS + W_LOADS) wait_vmcnt<DMAS + W_LOADS>();
-        else if (allowed >= W_LOADS) wait_vmcnt<W_LOADS>();
-        else if (allowed >= 2 * DMAS) wait_vmcnt<2 * DMAS>();
-        else if (allowed >= DMAS) wait_vmcnt<DMAS>();
-        else wait_vmcnt<0>();
-    };
 
     const int n_chunks = N / BK;   // host: N % BK == 0, N >= BK
-    issue(0, 0);
-    if (1 < n_chunks) issue(1, 1);
-    if (2 < n_chunks) issue(2, 2);
-    wait_allowing(DMAS * min(2, n_chunks - 1));
-    __builtin_amdgcn_s_barrier();
+    // my group's first chunk; every later one is requested right after the hand-over two chunks before it
+    if (g < n_chunks) {
+#pragma unroll
+        for (int i = 0; i < DMAS; ++i) issue_one(g, i);
+    }
+    if (g == 1) __builtin_amdgcn_s_barrier();                // barrier 0 is group 0's first hand-over
+    float wreg[RB][4];
+    const int col = d0 + wc * 32 + l32;                      // host: D % 64 == 0, so col < D
+    const int quad = 2 * kh + g;                             // accumulator entries 4 quad .. 4 quad + 3 are mine to finish
+    auto load_w = [&]() {
+#pragma unroll
+        for (int b = 0; b < RB; ++b)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int row = j0 + tile_row(b, 8 * quad + 4 * half + t);
+                wreg[b][t] = W[(int64_t)min(row, J - 1) * ldw + col];
+            }
+    };
+    if (g >= n_chunks) load_w();                             // a single chunk: group 1 has none, but finishes its quarter
     Frags fa, fb;
-    load_frags(0, 0, fa);
-    // The W entries this wavefront finishes (accumulator entries 8 kh .. 8 kh + 7 of every block): requested
-    // once the first fragments are on their way, consumed in the epilogue.  In counter order they sit after the
-    // copies of chunks 0-2 and before those of chunk 3: they count as younger operations while chunks 1 and 2
-    // are waited for, from chunk 3 on they are older and have retired.
-    float wreg[RB][8];
-    const int col = d0 + wc * 32 + l32;                     // host: D % 64 == 0, so col < D
-#pragma unroll
-    for (int b = 0; b < RB; ++b)
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int e = 8 * kh + t;
-            const int row = j0 + tile_row(b, 8 * (e / 4) + 4 * half + (e % 4));
-            wreg[b][t] = W[(int64_t)min(row, J - 1) * ldw + col];
-        }
-    // This is the only wavefront of its SIMD: nothing else hides an LDS wait or a barrier.  So the hand-over to
-    // the next chunk sits in the MIDDLE of a chunk's matrix work: first half multiplied while the second half of
-    // the fragments is read, then (my copies of chunk c + 1 have landed; barrier: everybody's have, and
-    // everybody is past chunk c - 1, whose stage the copies of chunk c + 3 now refill), second half multiplied
-    // while those copies are issued and the first fragments of chunk c + 1 are read.
-    // (the last chunk is written out on its own so that the loop body is one straight line: the LDS reads of
-    // the next set then need no more than the counted waits)
-    for (int c = 0; c + 1 < n_chunks; ++c) {
+    for (int c = g; c < n_chunks; c += 2) {
+        // hand-over to chunk c.  In counter order my copies of chunk c are followed by nothing but, once, the W
+        // loads (requested during my first chunk, i.e. after the copies of my second one)
+        if (c == g + 2) wait_vmcnt<W_LOADS>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();                        // barrier c
         const int st = c & 3;
-        multiply(fa, [&](int s) { load_step(st, 1, s, fb); });
-        wait_allowing((c + 2 < n_chunks ? DMAS : 0) + (c <= 1 ? W_LOADS : 0));
-        __builtin_amdgcn_s_barrier();
-        const bool more = c + 3 < n_chunks;
-        multiply(fb, [&](int s) {
+        const bool more = c + 2 < n_chunks;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) load_step(st, 0, s, fa);
+        if (c == g) {
+            // the copies of my second chunk first, then the W entries I finish: they have the whole contraction to arrive
             if (more) {
 #pragma unroll
-                for (int i = 0; i < DMAS; ++i)
-                    if (i * 4 / DMAS == s) issue_one(c + 3, (c + 3) & 3, i);
+                for (int i = 0; i < DMAS; ++i) issue_one(c + 2, i);
             }
-            load_step((c + 1) & 3, 0, s, fa);
-        });
+            load_w();
+            multiply(fa, [&](int s) { load_step(st, 1, s, fb); });
+        } else {
+            multiply(fa, [&](int s) {
+                if (more) {
+#pragma unroll
+                    for (int i = 0; i < DMAS; ++i)
+                        if (i * 4 / DMAS == s) issue_one(c + 2, i);
+                }
+                load_step(st, 1, s, fb);
+            });
+        }
+        if (c + 1 < n_chunks) __builtin_amdgcn_s_barrier();  // barrier c + 1: the other group's hand-over
+        multiply(fb, [](int) {});
     }
-    multiply(fa, [&](int s) { load_step((n_chunks - 1) & 3, 1, s, fb); });
-    multiply(fb, [](int) {});
 
-    // Exchange of partial sums: every stage has been read (barrier), the ring is free.  Slot of wavefront w,
-    // block b: two 16-byte items per lane = the eight accumulator entries the PARTNER finishes.
+    // Exchange of partial sums.  Everybody is done with the ring (barrier), which the exchange area overlays.
+    // Wavefront w, block b: the three quarters of its accumulator that the others finish, 16 bytes per lane
+    // each, at position t (t < quad) or t - 1 (t > quad) of its slot.
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     f32x4* xch = reinterpret_cast<f32x4*>(rks_lds);
-    auto finish = [&](auto KHc) {
-        constexpr int KH = decltype(KHc)::value;
+    auto finish = [&](auto Qc) {
+        constexpr int Q = decltype(Qc)::value;
 #pragma unroll
         for (int b = 0; b < RB; ++b)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                constexpr int e0 = 8 * (1 - KH);
-                xch[((wave * RB + b) * 2 + j) * 64 + lane] =
-                    f32x4{acc[b][e0 + 4 * j], acc[b][e0 + 4 * j + 1], acc[b][e0 + 4 * j + 2], acc[b][e0 + 4 * j + 3]};
+            for (int t = 0; t < 4; ++t) {
+                if (t == Q) continue;
+                const int pos = t < Q ? t : t - 1;
+                xch[((wave * RB + b) * 3 + pos) * 64 + lane] = f32x4{acc[b][4 * t], acc[b][4 * t + 1], acc[b][4 * t + 2], acc[b][4 * t + 3]};
             }
         __syncthreads();
-        const int partner = wave ^ 2;
 #pragma unroll
-        for (int b = 0; b < RB; ++b)
+        for (int b = 0; b < RB; ++b) {
+            f32x4 sum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const f32x4 p = xch[((partner * RB + b) * 2 + j) * 64 + lane];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int t = 4 * j + u, e = 8 * KH + t;
-                    const float sum = KH == 0 ? acc[b][e] + p[u] : p[u] + acc[b][e];      // (first half) + (second half)
-                    const int row = j0 + tile_row(b, 8 * (e / 4) + 4 * half + (e % 4));
-                    if (row < J) W[(int64_t)row * ldw + col] = prox_entry(wreg[b][t] + alpha * sum, prox_kind, prox_a);
+            for (int o = 0; o < 4; ++o) {                   // owners of quarters 0..3 = (kh, group) = (o / 2, o % 2), one fixed order
+                if (o == Q) {
+                    sum += f32x4{acc[b][4 * Q], acc[b][4 * Q + 1], acc[b][4 * Q + 2], acc[b][4 * Q + 3]};
+                } else {
+                    const int pw = (o % 2) * 4 + (o / 2) * 2 + wc;      // that owner's wavefront
+                    const int pos = Q < o ? Q : Q - 1;                  // where it put quarter Q
+                    sum += xch[((pw * RB + b) * 3 + pos) * 64 + lane];
                 }
             }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int row = j0 + tile_row(b, 8 * Q + 4 * half + t);
+                if (row < J) W[(int64_t)row * ldw + col] = prox_entry(wreg[b][t] + alpha * sum[t], prox_kind, prox_a);
+            }
+        }
     };
-    // both branches reach the same barrier inside: the condition is workgroup-wide per wavefront, not per lane
-    if (kh == 0) finish(std::integral_constant<int, 0>{});
-    else finish(std::integral_constant<int, 1>{});
+    switch (quad) {
+        case 0: finish(std::integral_constant<int, 0>{}); break;
+        case 1: finish(std::integral_constant<int, 1>{}); break;
+        case 2: finish(std::integral_constant<int, 2>{}); break;
+        default: finish(std::integral_constant<int, 3>{}); break;
+    }
 }
 
 // Row blocks per tile: as few row tiles as keep a tile within five row blocks.
@@ -250,15 +240,17 @@ bool reconstruct_ksplit_wins(int64_t J, int64_t D, int64_t other_blocks) {
     const int rb = ksplit_rb(J);
     if (rb < 3 || rb > 5) return false;
     const int64_t tiles = ((J + 32 * rb - 1) / (32 * rb)) * (D / kRksBN);
-    const int64_t waves_per_simd = (tiles * 4 + 1023) / 1024;
-    // rb half-blocks per wavefront: compare in half-block units
-    return 10 * waves_per_simd * rb <= 9 * 2 * other_blocks;
+    // a tile puts rb half-blocks (rb blocks through half of the pairs, as two wavefronts with a quarter each) on
+    // each of the four SIMDs of its compute unit: compare in half-block units
+    const int64_t tiles_per_simd = (tiles * 4 + 1023) / 1024;
+    return 10 * tiles_per_simd * rb <= 9 * 2 * other_blocks;
 }
 
 template <int RB>
 static hipError_t launch_ksplit(const ReconArgs& a, hipStream_t s) {
     constexpr int BM = 32 * RB;
-    constexpr size_t lds_bytes = (size_t)kRksStages * kRksBK * (BM + kRksBN) * sizeof(float);
+    constexpr size_t ring = (size_t)4 * kRksBK * (BM + kRksBN) * sizeof(float), exchange = (size_t)8 * RB * 3 * 1024;
+    constexpr size_t lds_bytes = ring > exchange ? ring : exchange;
     static std::atomic<bool> raised{false};
     if (lds_bytes > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_ksplit_kernel<RB>,
@@ -268,7 +260,7 @@ static hipError_t launch_ksplit(const ReconArgs& a, hipStream_t s) {
     }
     const int n_jb = (a.J + BM - 1) / BM, n_db = a.D / kRksBN;
     const int total = n_jb * n_db;
-    SFB_LAUNCH(reconstruct_apply_ksplit_kernel<RB>, dim3(total), dim3(kRksThreads), lds_bytes, s, a.w, a.ldw, a.u, a.ldu,
+    SFB_LAUNCH(reconstruct_apply_ksplit_kernel<RB>, dim3(total), dim3(512), lds_bytes, s, a.w, a.ldw, a.u, a.ldu,
                (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total, a.prox_kind, a.prox_a);
     return hipGetLastError();
 }

@@ -79,12 +79,14 @@ def test_single_block_reconstruct_variant(sfb, J, D, P, B):
 
 
 @pytest.mark.parametrize("J,D,P,B", [(600, 4096, 8, 128), (388, 1024, 4, 48), (256, 256, 1, 32), (96, 64, 2, 32),
-                                     (352, 192, 3, 32), (68, 64, 1, 128), (1000, 4096, 8, 64), (440, 128, 1, 64)])
+                                     (352, 192, 3, 32), (68, 64, 1, 128), (1000, 4096, 8, 64), (440, 128, 1, 64),
+                                     (600, 128, 5, 32), (104, 64, 7, 32)])
 def test_pair_split_reconstruct_variant(sfb, J, D, P, B):
-    """Variant 11 (tiles of 3 to 5 row blocks x 64 columns, the four wavefronts split the two column blocks and
-    every stage's pairs; D % 64 == 0, J % 4 == 0, N % 32 == 0): each of the three tile heights (J = 600, 388,
-    1000, 440: five row blocks; 256, 352: four; 96, 68: three), ragged last row tile and ragged last row block,
-    one to many stages (N = 32 ... 1024), a single tile."""
+    """Variant 11 (tiles of 3 to 5 row blocks x 64 columns, eight wavefronts = two column blocks x two halves of
+    every stage's pairs x two groups that take the stages in turn; D % 64 == 0, J % 4 == 0, N % 32 == 0): each of
+    the three tile heights (J = 600, 388, 1000, 440: five row blocks; 256, 352: four; 96, 68: three), ragged
+    last row tile and ragged last row block, one stage (N = 32: the second group has none), two, three (N = 96:
+    an odd count) and many (N = 1024), a single tile."""
     wl = workloads.make("mlr_medium", seed=11, J=J, D=D, P=P, B=B, steps=3, pool=2)
     run_chain(wl, 3, TOL32, plan=dict(recon_variant=11))
 
