@@ -315,7 +315,8 @@ SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32
  * 8: 64x128/2 staged by LDS-DMA where the shape allows, else as 0, 1; 9: 64x64/4, one 32x32 block per
  * wavefront, LDS-DMA, else as 8; 10: as 7 with 16-pair stages and two workgroups per compute unit;
  * 11: (96, 128 or 160)x64/8, the eight wavefronts split the two column blocks, every stage's factor
- * pairs and the stages themselves, LDS-DMA, for J whose 32-row blocks divide into tiles of 3 to 5, else as 9).
+ * pairs and the stages themselves, LDS-DMA, for J whose 32-row blocks divide into tiles of 3 to 5, else as 9;
+ * 12: 128x128/8, two wavefronts per 32-row strip that take the stages in turn, LDS-DMA, else as 7).
  * fwd_dma: bit 0 = stage the score contraction's tiles by LDS-DMA where the shape allows (else
  * always through registers); bit 1 = L2SVM scores by the dense contraction on the densified rows
  * instead of from the CSR entries; bit 2 = fp32 scores on the bf16 matrix cores, every fp32 operand split

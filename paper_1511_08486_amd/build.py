@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsfb.so")
 SOURCES = ["sfb_api.hip", "sfb_forward.hip", "sfb_factor.hip", "sfb_reconstruct.hip", "sfb_sparse.hip", "sfb_bf16.hip",
-           "sfb_ssp.hip", "sfb_forward_split.hip", "sfb_reconstruct_split.hip", "sfb_prox.hip", "sfb_reconstruct_small.hip", "sfb_reconstruct_ksplit.hip", "sfb_probe.hip", "sfb_fused.hip"]
+           "sfb_ssp.hip", "sfb_forward_split.hip", "sfb_reconstruct_split.hip", "sfb_prox.hip", "sfb_reconstruct_small.hip", "sfb_reconstruct_ksplit.hip", "sfb_reconstruct_pair.hip", "sfb_probe.hip", "sfb_fused.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fvisibility=hidden",
     # packed fp32 instructions are kept out of the generated code on purpose

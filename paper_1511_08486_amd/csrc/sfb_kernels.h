@@ -164,6 +164,9 @@ bool reconstruct_ksplit_ok(const ReconArgs& a);
 bool reconstruct_ksplit_wins(int64_t J, int64_t D, int64_t other_blocks);
 int reconstruct_ksplit_rows(int64_t J);
 hipError_t launch_reconstruct_ksplit(const ReconArgs& a, hipStream_t s);
+// 128 x 128 tiles with eight wavefronts in two groups that take the stages in turn (sfb_reconstruct_pair.hip)
+bool reconstruct_pair_ok(const ReconArgs& a);
+hipError_t launch_reconstruct_pair(const ReconArgs& a, hipStream_t s);
 // fp32 reconstruction as six bf16 term products per product (sfb_reconstruct_split.hip); 128 x 128 tiles
 bool reconstruct_split_ok(const ReconArgs& a);
 hipError_t launch_reconstruct_split(const ReconArgs& a, hipStream_t s);

@@ -552,8 +552,9 @@ static const ReconVariant kReconVariants[] = {
     {1, 2, 1, true},   // 9: 64 x 64, 4 wavefronts of one 32 x 32 block each, LDS-DMA staging (falls back to 8)
     {1, 4, 1, true},   // 10: as 7 with 16-pair stages and a register budget for two workgroups per compute unit
     {1, 2, 1, true},   // 11: (96..160) x 64, 8 wavefronts = 2 column blocks x 2 halves of every stage's pairs x 2 groups taking the stages in turn (falls back to 9)
+    {1, 4, 1, true},   // 12: 128 x 128, 8 wavefronts = 4 strips of 32 rows x 2 groups taking the stages in turn, LDS-DMA (falls back to 7)
 };
-constexpr int kSmallVariant = 9, kKsplitVariant = 11;
+constexpr int kSmallVariant = 9, kKsplitVariant = 11, kPairVariant = 12;
 constexpr int kNumReconVariants = sizeof(kReconVariants) / sizeof(kReconVariants[0]);
 
 int num_reconstruct_variants() { return kNumReconVariants; }
@@ -577,15 +578,11 @@ ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
         // wavefronts multiply clamped rows that are never stored)
         variant = J > 64 ? 8 : 7;
     }
-    // Several tiles per compute unit: 16-pair stages (48 KB of LDS) and a register budget that
-    // lets two workgroups share a compute unit, so that one multiplies while the other fetches
-    // its first stage or writes its tile back (measured, dense factors: J = 2000, D = 8192,
-    // N = 1024: 316 -> 277 us; 4096 x 4096, N = 512: 154 -> 142 us).  With one tile per compute
-    // unit there is nothing to overlap with and the shorter stages only cost (40.2 -> 42.6 us).
-    if (variant == 7) {
-        const int64_t tiles = ((J + 127) / 128) * ((D + kReconBN - 1) / kReconBN);
-        if (tiles >= 512) variant = 10;
-    }
+    // 128-row tiles: eight wavefronts, two per SIMD, in two groups that take the stages in turn, so that a
+    // hand-over between stages does not idle the matrix pipe (measured against the four-wavefront form:
+    // mlr_medium 41.9-44.7 -> 38.4-40.9 us; J = 2000, D = 8192, N = 1024 (four tiles per compute unit), where
+    // variant 10 lets two workgroups share a compute unit instead: 267-275 -> 262-263 us).
+    if (variant == 7) variant = kPairVariant;
     // single-block wavefronts where the lumps of four blocks would leave the busiest SIMD with
     // clearly more than its share (e.g. J = 600: 3 blocks instead of 4)
     if (kReconVariants[variant].dma) {
@@ -660,6 +657,10 @@ static hipError_t launch_recon_v(const ReconArgs& a, const ReconPlan& p, hipStre
 
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s) {
     ReconPlan q = p;
+    if (p.variant == kPairVariant) {
+        if (reconstruct_pair_ok(a)) return launch_reconstruct_pair(a, s);
+        q.variant = 7;
+    }
     if (p.variant == kKsplitVariant) {
         if (reconstruct_ksplit_ok(a)) return launch_reconstruct_ksplit(a, s);
         q.variant = kSmallVariant;

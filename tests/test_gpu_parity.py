@@ -61,12 +61,22 @@ def test_every_tile_variant(sfb, plan):
     run_chain(wl, 2, TOL32, plan=plan)
 
 
-@pytest.mark.parametrize("variant", [7, 8, 10])
+@pytest.mark.parametrize("variant", [7, 8, 10, 12])
 @pytest.mark.parametrize("J,D,P,B", [(520, 1024, 4, 48), (1000, 4096, 8, 64), (36, 256, 1, 32), (2000, 8192, 1, 16)])
 def test_lds_dma_reconstruct_variants(sfb, variant, J, D, P, B):
     """Shapes the LDS-DMA staging accepts (D % 128 == 0, J % 4 == 0, N % 32 == 0)."""
     wl = workloads.make("mlr_medium", seed=variant, J=J, D=D, P=P, B=B, steps=3, pool=2)
     run_chain(wl, 3, TOL32, plan=dict(recon_variant=variant))
+
+
+@pytest.mark.parametrize("J,D,P,B", [(260, 384, 3, 32), (128, 128, 2, 32), (132, 256, 5, 32), (4, 128, 1, 32),
+                                     (1000, 4096, 8, 64), (516, 512, 7, 32)])
+def test_two_group_reconstruct_variant(sfb, J, D, P, B):
+    """Variant 12 (128 x 128 tiles, eight wavefronts in two groups that take the stages of 32 pairs in turn;
+    D % 128 == 0, J % 4 == 0, N % 32 == 0): one stage (the second group has none), two, three, five, seven
+    (odd counts) and sixteen; ragged last strip and last row tile; a tile of four rows."""
+    wl = workloads.make("mlr_medium", seed=12, J=J, D=D, P=P, B=B, steps=3, pool=2)
+    run_chain(wl, 3, TOL32, plan=dict(recon_variant=12))
 
 
 @pytest.mark.parametrize("J,D,P,B", [(600, 4096, 8, 128), (520, 1024, 4, 48), (36, 256, 1, 32), (64, 64, 2, 32),

@@ -238,9 +238,9 @@ def test_launch_plans_of_the_benchmark_shapes(lib):
         assert r.value == grid, (model, J, D, r.value)
         assert k.value >= 1 and g.value >= 1
         # every variant of the table can be selected; one past the end cannot
-        for v in range(12):
+        for v in range(13):
             assert lib.sfb_set_plan(ctx, 0, 0, 0, v, -1) == 0
-        assert lib.sfb_set_plan(ctx, 0, 0, 0, 12, -1) == -1
+        assert lib.sfb_set_plan(ctx, 0, 0, 0, 13, -1) == -1
         lib.sfb_destroy(ctx)
 
 
