@@ -42,6 +42,14 @@ def test_padded_leading_dimensions(sfb, pad):
     run_chain(wl, 2, TOL32, pad=pad)
 
 
+@pytest.mark.parametrize("variant,J,D,P,B", [(12, 260, 384, 3, 32), (11, 388, 320, 2, 48), (9, 100, 192, 3, 32)])
+def test_padded_leading_dimensions_through_the_lds_dma_reconstructions(sfb, variant, J, D, P, B):
+    """ld = row length + 4 keeps the rows 16-byte aligned: the LDS-DMA kernels run (not their fallbacks) and must
+    honour ldw, ldu, ldv."""
+    wl = workloads.make("mlr_medium", seed=variant, J=J, D=D, P=P, B=B, steps=2, pool=2)
+    run_chain(wl, 2, TOL32, pad=4, plan=dict(recon_variant=variant))
+
+
 @pytest.mark.timeout(600)
 def test_mlr_medium_hundred_steps(sfb):
     wl = workloads.make("mlr_medium")
