@@ -131,7 +131,13 @@ def roofline_of(wl, per_kernel, split_k, traffic_table, pipelined):
 def bench_config(name, args, sfb, torch, workloads, traffic_table, cpu_seconds, extras=False):
     """One configuration: returns its record (the fields of the JSON line)."""
     dev = "cuda:0"
-    wl = workloads.make(name)
+    over = {}
+    if extras and args.shape:
+        # e.g. --config dml --shape J=600,D=780: the configuration's model and recipe at another size
+        over = {k: int(v) for k, v in (kv.split("=") for kv in args.shape.split(","))}
+        if set(over) - {"J", "D", "P", "B"}:
+            raise SystemExit("bench.py: --shape takes J, D, P and B only")
+    wl = workloads.make(name, **over)
     ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, dtype=wl.dtype, device=dev)
     if args.plan:
         vals = [int(x) for x in args.plan.split(",")] + [-1]
@@ -217,7 +223,7 @@ def bench_config(name, args, sfb, torch, workloads, traffic_table, cpu_seconds, 
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.model} J={wl.J} D={wl.D} P={wl.P} B={wl.B} eta={wl.eta}",
                    "plan": plan, "launch": launch},
-        "roofline": roofline_of(wl, per_kernel, plan["fwd_split_k"], traffic_table, pipelined),
+        "roofline": roofline_of(wl, per_kernel, plan["fwd_split_k"], {} if over else traffic_table, pipelined),
     }
     if extras:
         rec.update(extras_of(args, wl, ctx, sfb, torch, pool, W, W0, U, V, steps, warmup))
@@ -448,6 +454,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="single configuration only: record the pool's steps in a HIP graph and time replays")
     ap.add_argument("--plan", default="", help="single configuration only: fwd_bm,fwd_bn,split_k,recon_variant[,fwd_dma]")
+    ap.add_argument("--shape", default="",
+                    help="single configuration only: J=..,D=..,P=..,B=.. (any subset) in place of the configuration's "
+                         "own sizes, e.g. --config dml --shape J=600,D=780 (not a benchmark line: for ragged shapes)")
     ap.add_argument("--objective-every", type=int, default=0,
                     help="single configuration only: replay the steps from W0 (untimed) and report the mean per-sample "
                          "loss of the batch of every K-th step against samples processed")
@@ -478,8 +487,8 @@ def main():
         traffic_table = json.load(open(tpath))
 
     single = args.config != "all"
-    if not single and (args.graph or args.plan or args.prox or args.objective_every):
-        print("bench.py: --graph, --plan, --prox and --objective-every need --config NAME", file=sys.stderr)
+    if not single and (args.graph or args.plan or args.prox or args.objective_every or args.shape):
+        print("bench.py: --graph, --plan, --prox, --shape and --objective-every need --config NAME", file=sys.stderr)
         sys.exit(2)
     names = [args.config] if single else ALL_CONFIGS
     records, big = [], (None, None)

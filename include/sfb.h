@@ -107,8 +107,13 @@ SFB_API void sfb_destroy(sfb_ctx *ctx);
 
 /* Bytes of device workspace the context needs: the scores Z[N][J] as split-K partial sums,
  * plus, for bf16 contexts, the transposed bf16 copies of the factors that the
- * reconstruction multiplies (so sfb_reconstruct_apply needs the workspace too).  The caller
- * allocates at least that many bytes, 256-byte aligned, and registers them; the library
+ * reconstruction multiplies (so sfb_reconstruct_apply needs the workspace too).  fp32 contexts
+ * whose J is not a multiple of 4, D not one of 128 or P*B not one of 32 also count room for padded
+ * fp32 copies of U and V (rows of J rounded up to 4 and D rounded up to 128 floats, P*B rounded up
+ * to 32 rows; the same bytes as the partial scores, which are dead by then): with it registered
+ * their reconstruction runs the same matrix-core kernels as whole shapes, whatever the alignment
+ * of U, V and W, without it the slower element-by-element kernel (same results to rounding).  The
+ * caller allocates at least that many bytes, 256-byte aligned, and registers them; the library
  * uses the buffer until it is replaced or the ctx destroyed. */
 SFB_API sfb_status sfb_workspace_bytes(const sfb_ctx *ctx, size_t *bytes);
 SFB_API sfb_status sfb_set_workspace(sfb_ctx *ctx, void *dev, size_t bytes);
@@ -190,8 +195,8 @@ SFB_API sfb_status sfb_pipeline_info(const sfb_ctx *ctx, int32_t *fused, int32_t
 /*
  * sfb_step for callers that cannot allocate or register device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
- * same results as sfb_step, bit for bit, but the scratch the kernels need (split-K partial scores)
- * is a fixed array of SFB_NOALLOC_SCRATCH_BYTES of device memory inside the library, one copy per
+ * same results as sfb_step, bit for bit, but the scratch the kernels need (split-K partial scores,
+ * padded factor copies of ragged fp32 shapes, packed bf16 factors) is a fixed array of SFB_NOALLOC_SCRATCH_BYTES of device memory inside the library, one copy per
  * GPU, instead of the workspace registered with sfb_set_workspace (which this call neither needs
  * nor touches).  The call allocates and frees nothing, on the host or on the device.
  *   - SFB_ESCRATCH (nothing launched) if sfb_workspace_bytes(ctx) exceeds SFB_NOALLOC_SCRATCH_BYTES;
@@ -317,6 +322,8 @@ SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32
  * 11: (96, 128 or 160)x64/8, the eight wavefronts split the two column blocks, every stage's factor
  * pairs and the stages themselves, LDS-DMA, for J whose 32-row blocks divide into tiles of 3 to 5, else as 9;
  * 12: 128x128/8, two wavefronts per 32-row strip that take the stages in turn, LDS-DMA, else as 7).
+ * fp32 contexts that keep padded factor copies (see sfb_workspace_bytes) run 9, 11 or 12 on the copies:
+ * 8 stands for 9 there, 7 and 10 for 12, 11 outside its range of J for 9; 0-6 take the factors as they are.
  * fwd_dma: bit 0 = stage the score contraction's tiles by LDS-DMA where the shape allows (else
  * always through registers); bit 1 = L2SVM scores by the dense contraction on the densified rows
  * instead of from the CSR entries; bit 2 = fp32 scores on the bf16 matrix cores, every fp32 operand split

@@ -66,6 +66,8 @@ struct sfb_ctx {
     bool split_scores;             // use it where the shape allows
     bool split_recon;              // reconstruction with split-bf16 products where the shape allows
     ReconPlan recon;
+    ReconPlan recon_padded;        // the plan of the padded shape (ragged fp32 contexts: see padded_factors)
+    bool padded_factors;           // fp32 and J, D or P*B not what the LDS-DMA reconstructions take as they are
     FusedPlan fused;               // update fused with the next scores (bf16 contexts whose shape it covers)
     bool fused_ok, use_fused;
     void* ws;
@@ -106,6 +108,12 @@ size_t workspace_need(const sfb_ctx* c) {
     size_t need = scores_need(c);
     if (c->dtype == SFB_BF16) need += bf16_recon_workspace(c->J, c->D, (int64_t)c->P * c->B);
     if (c->fused_ok) need += fused_extra_workspace(c->D, (int64_t)c->P * c->B);   // staged next features, last
+    // ragged fp32 shapes: padded copies of the factors, made and used inside one reconstruction, when the
+    // partial scores (consumed by the factor kernel of the same call that wrote them) are dead: same bytes
+    if (c->padded_factors) {
+        const size_t pad = conform_workspace(c->J, c->D, (int64_t)c->P * c->B);
+        if (pad > need) need = pad;
+    }
     // the column projection of the proximal step reuses the front of the buffer between steps
     const size_t prox = prox_workspace(c->J, c->D);
     return need > prox ? need : prox;
@@ -290,7 +298,11 @@ sfb_status recon_launch(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64
     } else if (c->split_recon && reconstruct_split_ok(r)) {
         e = launch_reconstruct_split(r, c->stream);
     } else {
-        e = launch_reconstruct(r, c->recon, c->stream);
+        e = hipErrorNotSupported;
+        if (c->padded_factors && conformed_variant_ok(c->recon_padded.variant) && !reconstruct_takes_dma(r, c->recon) &&
+            c->ws != nullptr && c->ws_bytes >= workspace_need(c))
+            e = launch_reconstruct_conformed(r, c->recon_padded, c->ws, c->stream);
+        if (e == hipErrorNotSupported) e = launch_reconstruct(r, c->recon, c->stream);
     }
     if (e != hipSuccess) return hip_fail(c, e);
     return SFB_OK;
@@ -333,6 +345,12 @@ sfb_status sfb_create(sfb_ctx** out, sfb_model m, int64_t J, int64_t D, int32_t 
     c->split_scores = false;
     c->split_recon = false;
     c->recon = plan_reconstruct(J, D, (int64_t)P * B);
+    {
+        const int64_t N = (int64_t)P * B;
+        c->padded_factors = input_dtype == SFB_F32 &&
+                            !((J % 4) == 0 && J >= 4 && (D % 128) == 0 && (N % 32) == 0 && N >= 32);
+        c->recon_padded = plan_reconstruct_padded(J, D, N, -1);
+    }
     c->fused_ok = input_dtype == SFB_BF16 && m == SFB_MLR && fused_shape_ok(J, D, (int64_t)P * B);
     c->use_fused = true;
     c->fused = c->fused_ok ? plan_fused(J, D, (int64_t)P * B) : FusedPlan{};
@@ -641,7 +659,12 @@ sfb_status sfb_plan_info(const sfb_ctx* c, int32_t* fwd_split_k, int32_t* fwd_gr
     const FwdPlan& f = c->dtype == SFB_BF16 ? c->fwd_bf16 : c->fwd_all;
     if (fwd_split_k) *fwd_split_k = f.split_k;
     if (fwd_grid) *fwd_grid = f.grid;
-    if (recon_grid) *recon_grid = c->dtype == SFB_BF16 ? bf16_recon_grid(c->J, c->D) : c->recon.grid;
+    if (recon_grid) {
+        // ragged fp32 shapes run the padded shape's plan once a workspace is registered (recon_launch)
+        const bool padded = c->padded_factors && conformed_variant_ok(c->recon_padded.variant) && c->ws != nullptr &&
+                            c->ws_bytes >= workspace_need(c);
+        *recon_grid = c->dtype == SFB_BF16 ? bf16_recon_grid(c->J, c->D) : padded ? c->recon_padded.grid : c->recon.grid;
+    }
     return SFB_OK;
 }
 
@@ -662,7 +685,10 @@ sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_
     if (fwd_dma >= 0) c->use_fused = (fwd_dma & 16) == 0;       // bit 4 set: sfb_step_pipelined runs two separate passes
     finish_forward_plan(&p, (int64_t)c->P * c->B, c->J, c->D);
     c->fwd_all = p;
-    if (recon_variant >= 0) c->recon = plan_reconstruct_variant(c->J, c->D, recon_variant);
+    if (recon_variant >= 0) {
+        c->recon = plan_reconstruct_variant(c->J, c->D, recon_variant);
+        c->recon_padded = plan_reconstruct_padded(c->J, c->D, (int64_t)c->P * c->B, recon_variant);
+    }
     return SFB_OK;
 }
 

@@ -151,8 +151,29 @@ struct ReconArgs {
     bool use_mask, bf16;
     int prox_kind = 0;             // entrywise proximal operator applied to the updated entries
     float prox_a = 0.f;            //   before they are stored: see prox_entry (0 = none)
+    // Set by launch_reconstruct_conformed only: u and v are the padded copies made by
+    // conform_factors_kernel (16-byte aligned, J rounded up to 4 columns, D to Dp columns, N to whole
+    // stages of zero rows, dead workers' rows zero), W is whatever the caller passed: any
+    // alignment, any leading dimension, D columns.
+    bool conformed = false;
+    int Dp = 0;                    // columns of the padded v (a multiple of 128); 0: D itself
+    int tile_cols() const { return Dp > 0 ? Dp : D; }
 };
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s);
+// Ragged or misaligned fp32 factors through the LDS-DMA kernels: the factors are first copied
+// into `workspace` (conform_workspace(J, D, N) bytes, 256-byte aligned) with every row padded to
+// what those kernels assume, then the plan's kernel runs on the copies and updates W entry by
+// entry within its bounds.  `p` comes from plan_reconstruct_padded (variant < 0: the planner's choice
+// for the padded shape); returns hipErrorNotSupported (nothing launched) when that plan's kernel has
+// no such form (conformed_variant_ok(p.variant) is false: the register-staged variants).
+size_t conform_workspace(int64_t J, int64_t D, int64_t N);
+int64_t conform_cols(int64_t D);
+int64_t conform_rows(int64_t N);
+bool conformed_variant_ok(int variant);
+ReconPlan plan_reconstruct_padded(int64_t J, int64_t D, int64_t N, int variant);
+// True when launch_reconstruct(a, p) ends in one of the LDS-DMA kernels (nothing is launched).
+bool reconstruct_takes_dma(const ReconArgs& a, const ReconPlan& p);
+hipError_t launch_reconstruct_conformed(const ReconArgs& a, const ReconPlan& p, void* workspace, hipStream_t s);
 // 64 x 64 tiles, one 32 x 32 block per wavefront (sfb_reconstruct_small.hip): for shapes whose
 // block count leaves the larger tiles' busiest SIMD with clearly more work than the average
 bool reconstruct_small_ok(const ReconArgs& a);

@@ -655,6 +655,119 @@ static hipError_t launch_recon_v(const ReconArgs& a, const ReconPlan& p, hipStre
     return hipErrorInvalidValue;
 }
 
+// ---------------------------------------------------------------------------------------
+// Ragged or misaligned fp32 factors.  The LDS-DMA kernels want 16-byte aligned rows of whole
+// 16-byte items, whole column tiles and whole stages; shapes such as 600 x 780 (the metric
+// of Section 6 on 780 pixel features) or ten classes have none of that, and the
+// register-staged kernel takes them element by element with a bounds check each, several
+// times slower per factor pair.  The factors are small next to the work done with them
+// (N (J + D) numbers against N J D multiply-adds), so they are copied once into padded rows
+// -- J rounded up to 4 floats, D to whole 128-column tiles, N to whole stages of zero rows, a
+// dead worker's rows zero (selected, not multiplied: a dead slot may hold anything) -- and
+// the LDS-DMA kernels run on the copies.  W stays where it is: those kernels then take its
+// entries one by one, within J x D.
+// ---------------------------------------------------------------------------------------
+constexpr int kConformCols = 1024;   // columns of the concatenated [Jp + Dp] row per workgroup
+
+__global__ __launch_bounds__(256) void conform_factors_kernel(
+    const float* __restrict__ U, int64_t ldu, const float* __restrict__ V, int64_t ldv, float* __restrict__ Uc, int Jp,
+    float* __restrict__ Vc, int Dp, int N, int J, int D, int B, uint64_t live_mask, int use_mask) {
+    const int row = blockIdx.x;                               // < N rounded up to whole stages
+    bool live = row < N;
+    if (live && use_mask) live = ((live_mask >> (row / B)) & 1ull) != 0;      // host: a mask means at most 64 workers
+    const int c0 = blockIdx.y * kConformCols;
+#pragma unroll
+    for (int i = 0; i < kConformCols / 256; ++i) {
+        const int c = c0 + i * 256 + threadIdx.x;             // column of the row [ u (Jp) | v (Dp) ]
+        if (c < Jp) {
+            Uc[(int64_t)row * Jp + c] = (live && c < J) ? U[(int64_t)row * ldu + c] : 0.f;
+        } else if (c < Jp + Dp) {
+            const int d = c - Jp;
+            Vc[(int64_t)row * Dp + d] = (live && d < D) ? V[(int64_t)row * ldv + d] : 0.f;
+        }
+    }
+}
+
+int64_t conform_cols(int64_t D) { return (D + 127) / 128 * 128; }
+int64_t conform_rows(int64_t N) { return (N + kReconBK - 1) / kReconBK * kReconBK; }
+
+static size_t round_up_256(size_t x) { return (x + 255) / 256 * 256; }
+
+size_t conform_workspace(int64_t J, int64_t D, int64_t N) {
+    const size_t np = (size_t)conform_rows(N), jp = (size_t)((J + 3) / 4 * 4), dp = (size_t)conform_cols(D);
+    return round_up_256(np * jp * sizeof(float)) + round_up_256(np * dp * sizeof(float));
+}
+
+// The kernel that stands in for `variant` on padded factors: the 128 x 128 and the 64-row tiles map to
+// their eight-wavefront and single-block forms; 0 for the register-staged variants (no such form).
+static int conformed_variant(int variant) {
+    switch (variant) {
+        case 7: case 10: case kPairVariant: return kPairVariant;
+        case 8: case kSmallVariant: return kSmallVariant;
+        case kKsplitVariant: return kKsplitVariant;
+    }
+    return 0;
+}
+
+bool conformed_variant_ok(int variant) { return conformed_variant(variant) != 0; }
+
+ReconPlan plan_reconstruct_padded(int64_t J, int64_t D, int64_t N, int variant) {
+    const int64_t dp = conform_cols(D);
+    const ReconPlan p = variant >= 0 ? plan_reconstruct_variant(J, dp, variant) : plan_reconstruct(J, dp, conform_rows(N));
+    int v = conformed_variant(p.variant);
+    if (v == 0) return p;                                    // register-staged: taken as it is, on the factors as they are
+    if (v == kKsplitVariant) {
+        const int rows = reconstruct_ksplit_rows(J);
+        if (rows < 96 || rows > 160) v = kSmallVariant;      // what launch_reconstruct_conformed falls back to
+    }
+    return plan_reconstruct_variant(J, dp, v);
+}
+
+hipError_t launch_reconstruct_conformed(const ReconArgs& a, const ReconPlan& p, void* workspace, hipStream_t s) {
+    static_assert(kReconBK == 32, "stage depth of the kernels that take padded factors");
+    int variant = conformed_variant(p.variant);              // (plan_reconstruct_padded has already mapped it)
+    if (variant == 0 || a.bf16 || workspace == nullptr || ((uintptr_t)workspace % 256) != 0) return hipErrorNotSupported;
+    const int np = (int)conform_rows(a.N), jp = (a.J + 3) / 4 * 4, dp = (int)conform_cols(a.D);
+    ReconArgs c = a;
+    float* uc = (float*)workspace;
+    float* vc = (float*)((char*)workspace + round_up_256((size_t)np * jp * sizeof(float)));
+    c.u = uc; c.ldu = jp; c.v = vc; c.ldv = dp; c.N = np;
+    c.use_mask = false; c.live_mask = ~0ull;
+    c.conformed = true; c.Dp = dp;
+    if (variant == kKsplitVariant && !reconstruct_ksplit_ok(c)) variant = kSmallVariant;
+    if (variant == kPairVariant ? !reconstruct_pair_ok(c) : variant == kSmallVariant ? !reconstruct_small_ok(c) : false)
+        return hipErrorNotSupported;
+    hipLaunchKernelGGL(conform_factors_kernel, dim3(np, (jp + dp + kConformCols - 1) / kConformCols), dim3(256), 0, s,
+                       a.u, a.ldu, (const float*)a.v, a.ldv, uc, jp, vc, dp, a.N, a.J, a.D, a.B, a.live_mask,
+                       a.use_mask ? 1 : 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (variant == kPairVariant) return launch_reconstruct_pair(c, s);
+    if (variant == kKsplitVariant) return launch_reconstruct_ksplit(c, s);
+    return launch_reconstruct_small(c, s);
+}
+
+// True when launch_reconstruct(a, p) ends in one of the LDS-DMA kernels (the same chain of
+// fall-backs, without launching anything).
+bool reconstruct_takes_dma(const ReconArgs& a, const ReconPlan& p) {
+    int v = p.variant;
+    if (a.bf16 || !kReconVariants[v].dma) return false;
+    if (v == kPairVariant) {
+        if (reconstruct_pair_ok(a)) return true;
+        v = 7;
+    }
+    if (v == kKsplitVariant) {
+        if (reconstruct_ksplit_ok(a)) return true;
+        v = kSmallVariant;
+    }
+    if (v == kSmallVariant) {
+        if (reconstruct_small_ok(a)) return true;
+        v = 8;
+    }
+    if (v == 10 && dma_ok(a, 16)) return true;
+    return dma_ok(a, kReconBK);
+}
+
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s) {
     ReconPlan q = p;
     if (p.variant == kPairVariant) {

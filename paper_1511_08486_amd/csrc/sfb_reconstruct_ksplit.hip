@@ -64,10 +64,11 @@ __global__ __launch_bounds__(512) void reconstruct_apply_ksplit_kernel(
 
     const float* pu[U_LD];
     const float* pv[V_LD];
+    const int ju = (J + 3) & ~3;                             // host: a row of U holds J rounded up to 4 floats
 #pragma unroll
     for (int i = 0; i < U_LD; ++i) {
         const int idx = gtid + i * GT;
-        pu[i] = U + (int64_t)(idx / (BM / 4)) * ldu + min(j0 + (idx % (BM / 4)) * 4, J - 4);
+        pu[i] = U + (int64_t)(idx / (BM / 4)) * ldu + min(j0 + (idx % (BM / 4)) * 4, ju - 4);
     }
 #pragma unroll
     for (int i = 0; i < V_LD; ++i) {
@@ -128,7 +129,8 @@ __global__ __launch_bounds__(512) void reconstruct_apply_ksplit_kernel(
     }
     if (g == 1) __builtin_amdgcn_s_barrier();                // barrier 0 is group 0's first hand-over
     float wreg[RB][4];
-    const int col = d0 + wc * 32 + l32;                      // host: D % 64 == 0, so col < D
+    const int col = d0 + wc * 32 + l32;                      // beyond D only in the last tile of padded factors
+    const int colc = min(col, D - 1);
     const int quad = 2 * kh + g;                             // accumulator entries 4 quad .. 4 quad + 3 are mine to finish
     auto load_w = [&]() {
 #pragma unroll
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(512) void reconstruct_apply_ksplit_kernel(
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int row = j0 + tile_row(b, 8 * quad + 4 * half + t);
-                wreg[b][t] = W[(int64_t)min(row, J - 1) * ldw + col];
+                wreg[b][t] = W[(int64_t)min(row, J - 1) * ldw + colc];
             }
     };
     if (g >= n_chunks) load_w();                             // a single chunk: group 1 has none, but finishes its quarter
@@ -205,7 +207,7 @@ __global__ __launch_bounds__(512) void reconstruct_apply_ksplit_kernel(
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int row = j0 + tile_row(b, 8 * Q + 4 * half + t);
-                if (row < J) W[(int64_t)row * ldw + col] = prox_entry(wreg[b][t] + alpha * sum[t], prox_kind, prox_a);
+                if (row < J && col < D) W[(int64_t)row * ldw + col] = prox_entry(wreg[b][t] + alpha * sum[t], prox_kind, prox_a);
             }
         }
     };
@@ -227,8 +229,10 @@ static int ksplit_rb(int64_t J) {
 bool reconstruct_ksplit_ok(const ReconArgs& a) {
     auto al = [](const void* p, int64_t ld) { return ((uintptr_t)p % 16) == 0 && (ld % 4) == 0; };
     const int rb = ksplit_rb(a.J);
-    return !a.bf16 && !a.use_mask && al(a.u, a.ldu) && al(a.v, a.ldv) && (a.D % kRksBN) == 0 && (a.J % 4) == 0 &&
-           a.J >= 4 && (a.N % kRksBK) == 0 && a.N >= kRksBK && rb >= 3 && rb <= 5;
+    if (a.bf16 || a.use_mask || !al(a.u, a.ldu) || !al(a.v, a.ldv) || (a.tile_cols() % kRksBN) != 0 ||
+        (a.N % kRksBK) != 0 || a.N < kRksBK || rb < 3 || rb > 5)
+        return false;
+    return a.conformed || ((a.J % 4) == 0 && a.J >= 4);     // padded copies of U hold J rounded up to 4 columns
 }
 
 int reconstruct_ksplit_rows(int64_t J) { return 32 * ksplit_rb(J); }
@@ -258,7 +262,7 @@ static hipError_t launch_ksplit(const ReconArgs& a, hipStream_t s) {
         if (e != hipSuccess) return e;
         raised = true;
     }
-    const int n_jb = (a.J + BM - 1) / BM, n_db = a.D / kRksBN;
+    const int n_jb = (a.J + BM - 1) / BM, n_db = a.tile_cols() / kRksBN;
     const int total = n_jb * n_db;
     SFB_LAUNCH(reconstruct_apply_ksplit_kernel<RB>, dim3(total), dim3(512), lds_bytes, s, a.w, a.ldw, a.u, a.ldu,
                (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total, a.prox_kind, a.prox_a);

@@ -29,6 +29,9 @@ namespace sfb {
 
 constexpr int kRpBM = 128, kRpBN = 128, kRpBK = 32;
 
+// EDGE: W may have any alignment and leading dimension and end inside the last column tile (the factors
+// are then padded copies): its entries are read after the contraction and written one by one within bounds.
+template <bool EDGE>
 __global__ __launch_bounds__(512) void reconstruct_apply_pair_kernel(
     float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const float* __restrict__ V,
     int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total, int prox_kind, float prox_a) {
@@ -36,7 +39,7 @@ __global__ __launch_bounds__(512) void reconstruct_apply_pair_kernel(
     constexpr int U_LD = BK * BM / 4 / GT, V_LD = BK * BN / 4 / GT;           // 16-byte DMAs per thread and chunk
     constexpr int DMAS = U_LD + V_LD;
     constexpr int STAGE_FLOATS = BK * (BM + BN);
-    constexpr int W_LOADS = 8;                   // 16-byte loads: a wavefront finishes half of its strip's entries
+    constexpr int W_LOADS = EDGE ? 0 : 8;        // 16-byte loads in flight during the contraction: a wavefront finishes half of its strip's entries
     static_assert(U_LD == 4 && V_LD == 4, "tile / thread count mismatch");
     static_assert(DMAS + W_LOADS <= 63, "wait count encoding");
     extern __shared__ __attribute__((aligned(16))) float rp_lds[];            // 4 x (U tile, V tile); the exchange area overlays it
@@ -49,14 +52,15 @@ __global__ __launch_bounds__(512) void reconstruct_apply_pair_kernel(
     const int j0 = jb * BM, d0 = db * BN;
 
     // source of DMA i of a chunk: item idx = gtid + i * GT of the [k][128] tile in row-major order of
-    // 16-byte items.  Columns of U beyond J are clamped (host: J % 4 == 0, J >= 4): they feed rows of W
-    // that are never stored.
+    // 16-byte items.  Columns of U beyond J rounded up to 4 are clamped (host: a row of U holds that many
+    // floats): they feed rows of W that are never stored.
+    const int ju = (J + 3) & ~3;
     const float* pu[U_LD];
     const float* pv[V_LD];
 #pragma unroll
     for (int i = 0; i < U_LD; ++i) {
         const int idx = gtid + i * GT;
-        pu[i] = U + (int64_t)(idx / (BM / 4)) * ldu + min(j0 + (idx % (BM / 4)) * 4, J - 4);
+        pu[i] = U + (int64_t)(idx / (BM / 4)) * ldu + min(j0 + (idx % (BM / 4)) * 4, ju - 4);
     }
 #pragma unroll
     for (int i = 0; i < V_LD; ++i) {
@@ -112,16 +116,24 @@ __global__ __launch_bounds__(512) void reconstruct_apply_pair_kernel(
 
     // The W entries this wavefront finishes: accumulator entries 8 g .. 8 g + 7 of its four blocks = 8 rows x 4
     // consecutive columns per lane.
-    f32x4 wreg[W_LOADS];
+    f32x4 wreg[8];
     auto w_row = [&](int t) {
         const int e = 8 * g + t;
         return j0 + strip * 32 + 8 * (e / 4) + 4 * half + (e % 4);
     };
     auto load_w = [&]() {
 #pragma unroll
-        for (int t = 0; t < W_LOADS; ++t) wreg[t] = ldg4(W + (int64_t)min(w_row(t), J - 1) * ldw + d0 + 4 * l32);
+        for (int t = 0; t < 8; ++t) {
+            const float* wr = W + (int64_t)min(w_row(t), J - 1) * ldw;
+            if constexpr (EDGE) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) wreg[t][q] = wr[min(d0 + 4 * l32 + q, D - 1)];
+            } else {
+                wreg[t] = ldg4(wr + d0 + 4 * l32);
+            }
+        }
     };
-    if (g >= n_chunks) load_w();                             // a single chunk: group 1 has none, but finishes its half
+    if (!EDGE && g >= n_chunks) load_w();                    // a single chunk: group 1 has none, but finishes its half
     Frags fa, fb;
     for (int c = g; c < n_chunks; c += 2) {
         // hand-over to chunk c.  In counter order my copies of chunk c are followed by nothing but, once, the W
@@ -138,7 +150,7 @@ __global__ __launch_bounds__(512) void reconstruct_apply_pair_kernel(
 #pragma unroll
                 for (int i = 0; i < DMAS; ++i) issue_one(c + 2, i);
             }
-            load_w();
+            if (!EDGE) load_w();
             multiply(fa, [&](int s) { load_step(st, 1, s, fb); });
         } else {
             multiply(fa, [&](int s) {
@@ -156,6 +168,7 @@ __global__ __launch_bounds__(512) void reconstruct_apply_pair_kernel(
     // as [entry][lane] items of 16 bytes (the four blocks' values of one entry).
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
+    if (EDGE) load_w();
     f32x4* xch = reinterpret_cast<f32x4*>(rp_lds);
     auto finish = [&](auto Gc) {
         constexpr int G = decltype(Gc)::value;
@@ -173,8 +186,16 @@ __global__ __launch_bounds__(512) void reconstruct_apply_pair_kernel(
             const f32x4 mine = {acc[0][e], acc[1][e], acc[2][e], acc[3][e]};
             const f32x4 sum = G == 0 ? mine + p : p + mine;          // (even chunks) + (odd chunks)
             const int row = w_row(t);
-            if (row < J)
-                *reinterpret_cast<f32x4*>(W + (int64_t)row * ldw + d0 + 4 * l32) = prox_entry4(wreg[t] + alpha * sum, prox_kind, prox_a);
+            const f32x4 w = prox_entry4(wreg[t] + alpha * sum, prox_kind, prox_a);
+            if constexpr (EDGE) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = d0 + 4 * l32 + q;
+                    if (row < J && col < D) W[(int64_t)row * ldw + col] = w[q];
+                }
+            } else {
+                if (row < J) *reinterpret_cast<f32x4*>(W + (int64_t)row * ldw + d0 + 4 * l32) = w;
+            }
         }
     };
     if (g == 0) finish(std::integral_constant<int, 0>{});
@@ -183,24 +204,32 @@ __global__ __launch_bounds__(512) void reconstruct_apply_pair_kernel(
 
 bool reconstruct_pair_ok(const ReconArgs& a) {
     auto al = [](const void* p, int64_t ld) { return ((uintptr_t)p % 16) == 0 && (ld % 4) == 0; };
-    return !a.bf16 && !a.use_mask && al(a.w, a.ldw) && al(a.u, a.ldu) && al(a.v, a.ldv) && (a.D % kRpBN) == 0 &&
-           (a.J % 4) == 0 && a.J >= 4 && (a.N % kRpBK) == 0 && a.N >= kRpBK;
+    if (a.bf16 || a.use_mask || !al(a.u, a.ldu) || !al(a.v, a.ldv) || (a.tile_cols() % kRpBN) != 0 ||
+        (a.N % kRpBK) != 0 || a.N < kRpBK)
+        return false;
+    // padded copies of the factors go with the entry-by-entry form of the W accesses
+    return a.conformed || (al(a.w, a.ldw) && (a.J % 4) == 0 && a.J >= 4);
 }
 
-hipError_t launch_reconstruct_pair(const ReconArgs& a, hipStream_t s) {
+template <bool EDGE>
+static hipError_t launch_pair(const ReconArgs& a, hipStream_t s) {
     constexpr size_t lds_bytes = (size_t)4 * kRpBK * (kRpBM + kRpBN) * sizeof(float);      // 128 KB; the exchange needs 64 KB
     static std::atomic<bool> raised{false};
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_pair_kernel,
+        hipError_t e = hipFuncSetAttribute((const void*)reconstruct_apply_pair_kernel<EDGE>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    const int n_jb = (a.J + kRpBM - 1) / kRpBM, n_db = a.D / kRpBN;
+    const int n_jb = (a.J + kRpBM - 1) / kRpBM, n_db = a.tile_cols() / kRpBN;
     const int total = n_jb * n_db;
-    SFB_LAUNCH(reconstruct_apply_pair_kernel, dim3(total), dim3(512), lds_bytes, s, a.w, a.ldw, a.u, a.ldu,
+    SFB_LAUNCH(reconstruct_apply_pair_kernel<EDGE>, dim3(total), dim3(512), lds_bytes, s, a.w, a.ldw, a.u, a.ldu,
                (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total, a.prox_kind, a.prox_a);
     return hipGetLastError();
+}
+
+hipError_t launch_reconstruct_pair(const ReconArgs& a, hipStream_t s) {
+    return a.conformed ? launch_pair<true>(a, s) : launch_pair<false>(a, s);
 }
 
 }  // namespace sfb

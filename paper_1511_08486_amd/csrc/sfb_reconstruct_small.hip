@@ -44,14 +44,15 @@ __global__ __launch_bounds__(kRsmThreads) void reconstruct_apply_small_kernel(
     const int j0 = jb * BM, d0 = db * BN;
 
     // source of DMA i of a stage: item idx = tid + i * THREADS, row idx / 16 of the chunk,
-    // 16-byte item idx % 16 of the 64-float row.  Columns of U beyond J are clamped (host:
-    // J % 4 == 0, J >= 4): they feed rows of W that are never stored.
+    // 16-byte item idx % 16 of the 64-float row.  Columns of U beyond J rounded up to 4 are clamped
+    // (host: a row of U holds that many floats): they feed rows of W that are never stored.
+    const int ju = (J + 3) & ~3;
     const float* pu[U_LD];
     const float* pv[V_LD];
 #pragma unroll
     for (int i = 0; i < U_LD; ++i) {
         const int idx = tid + i * THREADS;
-        pu[i] = U + (int64_t)(idx / (BM / 4)) * ldu + min(j0 + (idx % (BM / 4)) * 4, J - 4);
+        pu[i] = U + (int64_t)(idx / (BM / 4)) * ldu + min(j0 + (idx % (BM / 4)) * 4, ju - 4);
     }
 #pragma unroll
     for (int i = 0; i < V_LD; ++i) {
@@ -115,11 +116,12 @@ __global__ __launch_bounds__(kRsmThreads) void reconstruct_apply_small_kernel(
     // DMAs of chunk 2 and those of chunk 3: while chunks 1 and 2 are waited for they count as
     // younger operations, from chunk 3 on they are older and have retired.
     float wreg[16];
-    const int col = d0 + wc * 32 + l32;                     // host: D % 64 == 0, so col < D
+    const int col = d0 + wc * 32 + l32;                     // beyond D only in the last tile of padded factors
+    const int colc = min(col, D - 1);
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
         const int row = j0 + wr * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-        wreg[e] = W[(int64_t)min(row, J - 1) * ldw + col];
+        wreg[e] = W[(int64_t)min(row, J - 1) * ldw + colc];
     }
     int st = 1;
     for (int c = 1; c < n_chunks; ++c) {
@@ -130,14 +132,16 @@ __global__ __launch_bounds__(kRsmThreads) void reconstruct_apply_small_kernel(
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
         const int row = j0 + wr * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-        if (row < J) W[(int64_t)row * ldw + col] = prox_entry(wreg[e] + alpha * acc[e], prox_kind, prox_a);
+        if (row < J && col < D) W[(int64_t)row * ldw + col] = prox_entry(wreg[e] + alpha * acc[e], prox_kind, prox_a);
     }
 }
 
 bool reconstruct_small_ok(const ReconArgs& a) {
     auto al = [](const void* p, int64_t ld) { return ((uintptr_t)p % 16) == 0 && (ld % 4) == 0; };
-    return !a.bf16 && !a.use_mask && al(a.u, a.ldu) && al(a.v, a.ldv) && (a.D % kRsmBN) == 0 && (a.J % 4) == 0 &&
-           a.J >= 4 && (a.N % kRsmBK) == 0 && a.N >= kRsmBK;
+    if (a.bf16 || a.use_mask || !al(a.u, a.ldu) || !al(a.v, a.ldv) || (a.tile_cols() % kRsmBN) != 0 ||
+        (a.N % kRsmBK) != 0 || a.N < kRsmBK)
+        return false;
+    return a.conformed || ((a.J % 4) == 0 && a.J >= 4);     // padded copies of U hold J rounded up to 4 columns
 }
 
 // 32 x 32 blocks the busiest SIMD carries when the work is handed out as `waves` wavefronts
@@ -156,7 +160,7 @@ bool reconstruct_small_wins(int64_t J, int64_t D, int big_bm, int big_waves) {
 }
 
 hipError_t launch_reconstruct_small(const ReconArgs& a, hipStream_t s) {
-    const int n_jb = (a.J + kRsmBM - 1) / kRsmBM, n_db = a.D / kRsmBN;
+    const int n_jb = (a.J + kRsmBM - 1) / kRsmBM, n_db = a.tile_cols() / kRsmBN;
     const int total = n_jb * n_db;
     SFB_LAUNCH(reconstruct_apply_small_kernel, dim3(total), dim3(kRsmThreads), 0, s, a.w, a.ldw, a.u, a.ldu,
                (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total, a.prox_kind, a.prox_a);

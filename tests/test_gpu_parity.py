@@ -51,6 +51,72 @@ def test_padded_leading_dimensions_through_the_lds_dma_reconstructions(sfb, vari
 
 
 @pytest.mark.timeout(600)
+@pytest.mark.parametrize("variant", [-1, 9, 11, 12, 7, 8, 10, 0])
+@pytest.mark.parametrize("name,over", [("dml", dict(J=600, D=780, P=4, B=40)),      # the metric of Section 6 on 780 features
+                                       ("mlr_tiny", dict(J=10, D=784, P=4, B=16)),   # ten classes on 784 pixels
+                                       ("mlr_tiny", dict(J=1001, D=260, P=3, B=21)),
+                                       ("l2svm", dict(J=130, D=515, P=2, B=33, density=0.05))])
+def test_ragged_fp32_shapes_through_padded_factor_copies(sfb, name, over, variant):
+    """J % 4, D % 128 or P*B % 32 not zero: the reconstruction copies the factors into padded rows and
+    runs its LDS-DMA kernels on the copies (the planner's choice for the padded shape, or the
+    single-block / two-group / pair kernel that stands for the variant asked for; variant 0 is
+    register-staged and takes the factors as they are).  W has a leading dimension of D + 1."""
+    wl = make_clear_of_kink(name, 77, 2, steps=2, pool=2, **over)
+    run_chain(wl, 2, TOL32, pad=1, plan=None if variant < 0 else dict(recon_variant=variant))
+
+
+def test_padded_factor_copies_are_what_the_reconstruction_reads(sfb):
+    """Ragged shape: after sfb_reconstruct_apply the workspace holds the factors as [32 x 40] and
+    [32 x 256] (37 -> 40 columns, 203 -> 256, 15 -> 32 rows), zero outside, and a dead worker's rows
+    zero whatever its slot held.  A register-staged variant, or a shape the kernels take as it is,
+    leaves the workspace alone."""
+    dev = "cuda:0"
+    J, D, P, B, eta = 37, 203, 3, 5, 0.1
+    N, Np, Jp, Dp = P * B, 32, 40, 256
+    rng = np.random.default_rng(5)
+    W0 = rng.standard_normal((J, D)).astype(np.float32)
+    Uh = rng.standard_normal((N, J)).astype(np.float32)
+    Vh = rng.standard_normal((N, D)).astype(np.float32)
+    active = [1, 0, 1]
+    Uh_dead = Uh.copy()
+    Uh_dead[B:2 * B] = np.nan                                   # what a dead worker's slot may hold
+    ctx = sfb.Sfb("mlr", J, D, P, B, device=dev)
+    assert ctx.workspace_bytes() >= (Np * Jp + Np * Dp) * 4
+    ws = ctx._ws.view(torch.float32)
+    for variant, mask in ((-1, None), (-1, active), (0, None)):
+        if variant >= 0:
+            ctx.set_plan(recon_variant=variant)
+            ws = ctx._ws.view(torch.float32)
+        ws.fill_(float("nan"))
+        W = torch.from_numpy(W0).to(dev)
+        U = torch.from_numpy(Uh_dead if mask else Uh).to(dev)
+        V = torch.from_numpy(Vh).to(dev)
+        ctx.reconstruct_apply(W, U, V, eta, active=mask)
+        ctx.sync()
+        live = np.repeat(np.asarray(mask if mask else [1] * P, dtype=bool), B)
+        dW = oracle.delta_w(np.where(live[:, None], Uh, 0.0), Vh.astype(np.float64), P, B, active=mask)
+        assert_close(W.cpu().numpy(), oracle.apply_update(W0.astype(np.float64), dW, eta), TOL32, f"W, variant {variant}")
+        if variant == 0:
+            assert bool(torch.isnan(ws).all())
+            continue
+        Uc = ws[:Np * Jp].view(Np, Jp).cpu().numpy()
+        Vc = ws[Np * Jp:Np * Jp + Np * Dp].view(Np, Dp).cpu().numpy()     # 32 * 40 * 4 bytes is a multiple of 256
+        want_u, want_v = np.zeros((Np, Jp), np.float32), np.zeros((Np, Dp), np.float32)
+        want_u[:N, :J] = np.where(live[:, None], Uh, 0.0)
+        want_v[:N, :D] = np.where(live[:, None], Vh, 0.0)
+        assert np.array_equal(Uc, want_u) and np.array_equal(Vc, want_v)
+    ctx.close()
+    whole = sfb.Sfb("mlr", 64, 128, 2, 16, device=dev)
+    ws = whole._ws.view(torch.float32)
+    ws.fill_(float("nan"))
+    W = torch.zeros((64, 128), device=dev)
+    whole.reconstruct_apply(W, torch.ones((32, 64), device=dev), torch.ones((32, 128), device=dev), eta)
+    whole.sync()
+    assert bool(torch.isnan(ws).all())
+    assert torch.equal(W, torch.full((64, 128), -eta * 32 / 16, device=dev))
+    whole.close()
+
+
 def test_mlr_medium_hundred_steps(sfb):
     wl = workloads.make("mlr_medium")
     worst = run_chain(wl, wl.steps, TOL32, check_every=7)

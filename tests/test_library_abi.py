@@ -53,6 +53,45 @@ def test_create_validates_arguments(lib):
     lib.sfb_destroy(ctx)
 
 
+def test_ragged_fp32_contexts_reserve_room_for_padded_factor_copies(lib):
+    """A context whose J, D or P*B is not what the LDS-DMA reconstructions take as they are (J % 4,
+    D % 128, P*B % 32) asks for room for padded copies of the factors: rows of J rounded up to 4 and D
+    rounded up to 128 floats, P*B rounded up to 32 rows, each copy rounded to 256 bytes, overlaying the
+    partial scores.  Whole shapes and bf16 contexts ask for what they asked for before."""
+    import paper_1511_08486_amd as sfb
+    need, k, g, r = C.c_size_t(), C.c_int32(), C.c_int32(), C.c_int32()
+
+    def ask(model, J, D, P, B, dtype):
+        ctx = C.c_void_p()
+        assert lib.sfb_create(C.byref(ctx), model, J, D, P, B, dtype, None) == 0
+        assert lib.sfb_workspace_bytes(ctx, C.byref(need)) == 0
+        assert lib.sfb_plan_info(ctx, C.byref(k), C.byref(g), C.byref(r)) == 0
+        lib.sfb_destroy(ctx)
+        return need.value, k.value
+
+    def padded(J, D, N):
+        up = lambda x, m: (x + m - 1) // m * m
+        return up(up(N, 32) * up(J, 4) * 4, 256) + up(up(N, 32) * up(D, 128) * 4, 256)
+
+    def expect(J, D, N, split, pad):
+        up = lambda x, m: (x + m - 1) // m * m
+        scores = up(split * N * up(J, 4) * 4, 256)
+        return max(scores, padded(J, D, N)) if pad else scores
+
+    got, split = ask(sfb.SFB_DML, 600, 780, 8, 128, sfb.SFB_F32)           # the metric of Section 6 on 780 features
+    assert got == expect(600, 780, 1024, split, True)
+    got, split = ask(sfb.SFB_MLR, 10, 100, 4, 16, sfb.SFB_F32)             # the smallest benchmark shape: the copies decide
+    assert got == expect(10, 100, 64, split, True) == padded(10, 100, 64) == 64 * 12 * 4 + 64 * 128 * 4
+    got, split = ask(sfb.SFB_MLR, 10, 784, 8, 64, sfb.SFB_F32)             # ten classes on 784 pixels
+    assert got == expect(10, 784, 512, split, True) == padded(10, 784, 512)
+    got, split = ask(sfb.SFB_MLR, 1000, 4096, 8, 60, sfb.SFB_F32)          # 480 rows: whole stages, nothing to pad
+    assert got == expect(1000, 4096, 480, split, False)
+    got, split = ask(sfb.SFB_MLR, 1000, 4096, 8, 61, sfb.SFB_F32)          # 488 rows
+    assert got == expect(1000, 4096, 488, split, True) == padded(1000, 4096, 488)
+    got32, _ = ask(sfb.SFB_MLR, 300, 1004, 3, 30, sfb.SFB_F32)             # ragged in every way
+    assert got32 >= padded(300, 1004, 90)
+
+
 def test_calls_reject_bad_arguments_before_launching(lib):
     """Fake non-null pointers are safe here: validation fails first, nothing is launched."""
     import paper_1511_08486_amd as sfb
