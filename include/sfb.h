@@ -112,7 +112,8 @@ SFB_API void sfb_destroy(sfb_ctx *ctx);
  * fp32 copies of U and V (rows of J rounded up to 4 and D rounded up to 128 floats, P*B rounded up
  * to 32 rows; the same bytes as the partial scores, which are dead by then): with it registered
  * their reconstruction runs the same matrix-core kernels as whole shapes, whatever the alignment
- * of U, V and W, without it the slower element-by-element kernel (same results to rounding).  The
+ * of U, V and W, without it the slower element-by-element kernel (same results to rounding).  A
+ * call with a dead worker (`active`) likewise takes a masked copy of U in the partial scores' bytes.  The
  * caller allocates at least that many bytes, 256-byte aligned, and registers them; the library
  * uses the buffer until it is replaced or the ctx destroyed. */
 SFB_API sfb_status sfb_workspace_bytes(const sfb_ctx *ctx, size_t *bytes);

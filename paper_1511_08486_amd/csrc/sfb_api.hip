@@ -298,10 +298,16 @@ sfb_status recon_launch(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64
     } else if (c->split_recon && reconstruct_split_ok(r)) {
         e = launch_reconstruct_split(r, c->stream);
     } else {
+        // calls that would end in the register-staged kernel first try a copy of the factors that the LDS-DMA
+        // kernels accept: padded ones for ragged shapes, U with a dead worker's rows zeroed for a masked call
+        // (N x ceil4(J) floats: never more than the partial scores, whose bytes it takes)
         e = hipErrorNotSupported;
-        if (c->padded_factors && conformed_variant_ok(c->recon_padded.variant) && !reconstruct_takes_dma(r, c->recon) &&
-            c->ws != nullptr && c->ws_bytes >= workspace_need(c))
-            e = launch_reconstruct_conformed(r, c->recon_padded, c->ws, c->stream);
+        if (c->ws != nullptr && c->ws_bytes >= workspace_need(c) && !reconstruct_takes_dma(r, c->recon)) {
+            if (c->padded_factors && conformed_variant_ok(c->recon_padded.variant))
+                e = launch_reconstruct_conformed(r, c->recon_padded, c->ws, c->stream);
+            else if (r.use_mask && masked_workspace(c->J, r.N) <= scores_need(c))
+                e = launch_reconstruct_masked(r, c->recon, c->ws, c->stream);
+        }
         if (e == hipErrorNotSupported) e = launch_reconstruct(r, c->recon, c->stream);
     }
     if (e != hipSuccess) return hip_fail(c, e);

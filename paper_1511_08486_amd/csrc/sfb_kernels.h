@@ -174,6 +174,11 @@ ReconPlan plan_reconstruct_padded(int64_t J, int64_t D, int64_t N, int variant);
 // True when launch_reconstruct(a, p) ends in one of the LDS-DMA kernels (nothing is launched).
 bool reconstruct_takes_dma(const ReconArgs& a, const ReconPlan& p);
 hipError_t launch_reconstruct_conformed(const ReconArgs& a, const ReconPlan& p, void* workspace, hipStream_t s);
+// A dead worker (a.use_mask) in a call that would otherwise end in an LDS-DMA kernel: U is copied into
+// `workspace` (masked_workspace(J, N) bytes, 256-byte aligned) with the dead workers' rows as zeros and the
+// plan's kernel runs on the copy without a mask; hipErrorNotSupported (nothing launched) otherwise.
+size_t masked_workspace(int64_t J, int64_t N);
+hipError_t launch_reconstruct_masked(const ReconArgs& a, const ReconPlan& p, void* workspace, hipStream_t s);
 // 64 x 64 tiles, one 32 x 32 block per wavefront (sfb_reconstruct_small.hip): for shapes whose
 // block count leaves the larger tiles' busiest SIMD with clearly more work than the average
 bool reconstruct_small_ok(const ReconArgs& a);

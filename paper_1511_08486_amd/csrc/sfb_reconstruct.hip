@@ -723,6 +723,27 @@ ReconPlan plan_reconstruct_padded(int64_t J, int64_t D, int64_t N, int variant) 
     return plan_reconstruct_variant(J, dp, v);
 }
 
+// A dead worker in a shape the LDS-DMA kernels take as it is: only U is copied (N x J rounded up to 4
+// floats, the dead workers' rows as zeros), V and W are used where they are, and the plan's kernel
+// runs without a mask.  hipErrorNotSupported (nothing launched) when the same call without its mask
+// would not end in an LDS-DMA kernel either.
+size_t masked_workspace(int64_t J, int64_t N) { return round_up_256((size_t)N * (size_t)((J + 3) / 4 * 4) * sizeof(float)); }
+
+hipError_t launch_reconstruct_masked(const ReconArgs& a, const ReconPlan& p, void* workspace, hipStream_t s) {
+    if (!a.use_mask || a.bf16 || workspace == nullptr || ((uintptr_t)workspace % 256) != 0) return hipErrorNotSupported;
+    const int jp = (a.J + 3) / 4 * 4;
+    ReconArgs c = a;
+    float* uc = (float*)workspace;
+    c.u = uc; c.ldu = jp;
+    c.use_mask = false; c.live_mask = ~0ull;
+    if (!reconstruct_takes_dma(c, p)) return hipErrorNotSupported;
+    hipLaunchKernelGGL(conform_factors_kernel, dim3(a.N, (jp + kConformCols - 1) / kConformCols), dim3(256), 0, s, a.u,
+                       a.ldu, (const float*)a.v, a.ldv, uc, jp, (float*)nullptr, 0, a.N, a.J, a.D, a.B, a.live_mask, 1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_reconstruct(c, p, s);
+}
+
 hipError_t launch_reconstruct_conformed(const ReconArgs& a, const ReconPlan& p, void* workspace, hipStream_t s) {
     static_assert(kReconBK == 32, "stage depth of the kernels that take padded factors");
     int variant = conformed_variant(p.variant);              // (plan_reconstruct_padded has already mapped it)

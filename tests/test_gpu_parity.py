@@ -117,6 +117,44 @@ def test_padded_factor_copies_are_what_the_reconstruction_reads(sfb):
     whole.close()
 
 
+def test_a_dead_worker_in_a_whole_shape_goes_through_a_masked_copy_of_u(sfb):
+    """Whole shape, one dead worker: the reconstruction copies U with that worker's rows as zeros
+    (whatever the slot held) into the front of the workspace and runs its usual kernel without a
+    mask.  With V off the 16-byte grid the call falls back to the register-staged kernel, which
+    carries the mask itself and leaves the workspace alone.  Both match the oracle."""
+    dev = "cuda:0"
+    J, D, P, B, eta = 260, 512, 4, 32, 0.1
+    N = P * B
+    rng = np.random.default_rng(9)
+    W0 = rng.standard_normal((J, D)).astype(np.float32)
+    Uh = rng.standard_normal((N, J)).astype(np.float32)
+    Vh = rng.standard_normal((N, D)).astype(np.float32)
+    active = [1, 1, 0, 1]
+    live = np.repeat(np.asarray(active, dtype=bool), B)
+    U_masked = np.where(live[:, None], Uh, np.float32(0))
+    want = oracle.apply_update(W0.astype(np.float64), oracle.delta_w(U_masked, Vh, P, B, active=active), eta)
+    Uh_dead = np.where(live[:, None], Uh, np.float32("nan"))
+    ctx = sfb.Sfb("mlr", J, D, P, B, device=dev)
+    ws = ctx._ws.view(torch.float32)
+    for misaligned in (False, True):
+        ws.fill_(float("nan"))
+        W = torch.from_numpy(W0).to(dev)
+        U = torch.from_numpy(Uh_dead).to(dev)
+        if misaligned:
+            V = torch.empty(N * D + 1, dtype=torch.float32, device=dev)[1:].view(N, D)
+            V.copy_(torch.from_numpy(Vh))
+        else:
+            V = torch.from_numpy(Vh).to(dev)
+        ctx.reconstruct_apply(W, U, V, eta, active=active)
+        ctx.sync()
+        assert_close(W.cpu().numpy(), want, TOL32, f"W, dead worker, V {'off' if misaligned else 'on'} the 16-byte grid")
+        if misaligned:
+            assert bool(torch.isnan(ws).all())
+        else:
+            assert np.array_equal(ws[:N * J].view(N, J).cpu().numpy(), U_masked)
+    ctx.close()
+
+
 def test_mlr_medium_hundred_steps(sfb):
     wl = workloads.make("mlr_medium")
     worst = run_chain(wl, wl.steps, TOL32, check_every=7)
