@@ -310,7 +310,8 @@ SFB_API int sfb_last_hip_error(const sfb_ctx *ctx);
  * enable it while the stream is being captured into a graph); sfb_kernel_time_ms synchronises
  * and returns the accumulated milliseconds and launch count of kernel family `which`
  * (0 = scores, 1 = factor u, 2 = reconstruct-apply: the contraction, without the bf16 path's
- * operand-packing kernel, 3 = CSR densify / stream copy, 4 = proximal step) since the last reset.
+ * operand-packing kernel, 3 = CSR densify / stream copy, 4 = proximal step, 5 = the one-pass update +
+ * next scores kernel of sfb_step_pipelined, without its packing kernel) since the last reset.
  */
 SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32_t *fwd_grid,
                          int32_t *recon_grid);

@@ -15,7 +15,7 @@
 using namespace sfb;
 
 namespace {
-constexpr int kFamilies = 5;  // 0 scores, 1 factor u, 2 reconstruct-apply, 3 sparse helpers, 4 proximal step
+constexpr int kFamilies = 6;  // 0 scores, 1 factor u, 2 reconstruct-apply, 3 sparse helpers, 4 proximal step, 5 one-pass update + next scores
 struct EventPair { hipEvent_t a, b; };
 
 // Scratch of the entry point that allocates nothing (sfb_step_noalloc): device memory that belongs
@@ -484,7 +484,7 @@ sfb_status sfb_step_pipelined(sfb_ctx* c, float* W, int64_t ldw, float* U, int64
             char* ws_factors = (char*)c->ws + scores_need(c);
             char* ws_next = ws_factors + bf16_recon_workspace(c->J, c->D, N);
             {
-                Timed t(c, 2);
+                Timed t(c, 5);
                 hipError_t e = launch_fused(f, c->fused, ws_factors, ws_next, c->stream);
                 if (e != hipSuccess) return hip_fail(c, e);
             }
