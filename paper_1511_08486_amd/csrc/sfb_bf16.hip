@@ -392,16 +392,23 @@ FwdPlan plan_forward_bf16(int64_t n_rows, int64_t J, int64_t D) {
     p.bn = kBfFwdBN;
     const int64_t tiles = ((n_rows + kBfFwdBM - 1) / kBfFwdBM) * ((J + kBfFwdBN - 1) / kBfFwdBN);
     const int64_t chunks = D / kBfFwdBK > 0 ? D / kBfFwdBK : 1;
-    // One workgroup per compute unit is resident (the stage ring fills the LDS), so the time
-    // goes as rounds-of-256 x 1/slices: take the slice count that wastes the fewest rounds,
-    // charging a little for every extra partial-sum round trip.
-    const int64_t s_max = chunks / 8 > 0 ? (chunks / 8 < 8 ? chunks / 8 : 8) : 1;
+    // One workgroup per compute unit is resident (the stage ring fills the LDS) and pulls its rows of W at what
+    // one compute unit's outstanding misses allow, about 25 GB/s; all of them together at no more than the
+    // pass's share of HBM, about 4.5 TB/s; every slice costs one more write and read of the partial scores.
+    // In microseconds (bytes / 1e6 per TB/s):
+    const int64_t s_max = chunks / 8 > 0 ? (chunks / 8 < 32 ? chunks / 8 : 32) : 1;
+    // (the sample blocks that share rows of W run on one die and fetch them into its L2 once)
+    const double w_bytes = (double)((J + kBfFwdBN - 1) / kBfFwdBN * kBfFwdBN) * (double)D * 4.0;
     int64_t best = 1;
     double best_cost = 1e30;
     for (int64_t s = 1; s <= s_max; ++s) {
+        const int64_t k = (chunks + s - 1) / s * kBfFwdBK;                    // columns per slice
         const double rounds = (double)((tiles * s + 255) / 256);
-        const double cost = rounds / (double)s + 0.02 * (double)s;
-        if (cost < best_cost - 1e-12) { best_cost = cost; best = s; }
+        const double per_cu = rounds * (double)kBfFwdBN * (double)k * 4.0 / 25e3;
+        const double hbm = w_bytes / 4.5e6;
+        const double partials = (double)s * (double)n_rows * (double)J * 8.0 / 4e6;
+        const double cost = (per_cu > hbm ? per_cu : hbm) + partials;
+        if (cost < best_cost * (1.0 - 1e-9)) { best_cost = cost; best = s; }
     }
     int64_t s = best;
     const int64_t per = (chunks + s - 1) / s;
