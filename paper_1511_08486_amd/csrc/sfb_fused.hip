@@ -389,19 +389,33 @@ bool fused_shape_ok(int64_t J, int64_t D, int64_t N) {
     return (N == 128 || N == 256 || N == 512) && D % kFuCols == 0 && D >= kFuCols && J >= 1;
 }
 
-// Column slices: as many as bring the grid to one workgroup per compute unit, each at least 8 tiles long.
+// Column slices, each at least 8 tiles long.  One workgroup per compute unit is resident, so the launch takes
+// rounds-of-256-workgroups x (tiles of a slice + the fixed cost of a workgroup: its rows of (alpha u)^T in, its
+// partial scores out, about 7 tile times), and every slice costs one more write and read of the partial scores
+// (N x J x 8 bytes at about 4 TB/s, a tile taking about 2.7 us).  Up to 85 bands that is one round of as many
+// slices as fit; beyond (J = 11000: 86 bands) two rounds of shorter slices beat one round that leaves a third of
+// the compute units idle.  Ties go to fewer slices.
 FusedPlan plan_fused(int64_t J, int64_t D, int64_t N) {
     FusedPlan p{};
     p.n_bands = (int)((J + kFuBand - 1) / kFuBand);
     const int64_t tiles = D / kFuCols;
-    int64_t s = 256 / p.n_bands;
-    if (s > tiles / 8) s = tiles / 8;
-    if (s < 1) s = 1;
-    const int64_t per = (tiles + s - 1) / s;
+    int64_t s_max = tiles / 8;
+    if (s_max < 1) s_max = 1;
+    if (s_max > 64) s_max = 64;
+    const double slice_cost = (double)N * (double)J * 8.0 / 4e6 / 2.7;        // in tile times
+    int64_t best = 1;
+    double best_cost = 1e300;
+    for (int64_t s = 1; s <= s_max; ++s) {
+        const int64_t per = (tiles + s - 1) / s;
+        if ((tiles + per - 1) / per != s) continue;                           // the same cut as a smaller count
+        const double rounds = (double)((p.n_bands * s + 255) / 256);
+        const double cost = rounds * ((double)per + 7.0) + (double)s * slice_cost;
+        if (cost < best_cost * (1.0 - 1e-9)) { best_cost = cost; best = s; }
+    }
+    const int64_t per = (tiles + best - 1) / best;
     p.slices = (int)((tiles + per - 1) / per);
     p.k_slice = (int)(per * kFuCols);
     p.grid = p.n_bands * p.slices;
-    (void)N;
     return p;
 }
 

@@ -21,6 +21,7 @@ TOLBF = 2e-2
     (1000, 2048, 16, 32, None),        # N = 512: the benchmark's worker layout
     (128, 32, 4, 32, None),            # one band, one tile
     (260, 1056, 16, 32, [1] * 5 + [0] + [1] * 10),   # a dead worker's pending factors contribute nothing; 33 tiles
+    (33000, 256, 4, 32, None),         # 258 bands: more workgroups than compute units, the launch takes two rounds
 ])
 def test_fused_chain_matches_the_oracle(J, D, P, B, active):
     wl = workloads.make("mlr_large", seed=J + D, J=J, D=D, P=P, B=B, steps=4, pool=3)
