@@ -327,8 +327,9 @@ SFB_API sfb_status sfb_plan_info(const sfb_ctx *ctx, int32_t *fwd_split_k, int32
  * fp32 contexts that keep padded factor copies (see sfb_workspace_bytes) run 9, 11 or 12 on the copies:
  * 8 stands for 9 there, 7 and 10 for 12, 11 outside its range of J for 9; 0-6 take the factors as they are.
  * fwd_dma: bit 0 = stage the score contraction's tiles by LDS-DMA where the shape allows (else
- * always through registers); bit 1 = L2SVM scores by the dense contraction on the densified rows
- * instead of from the CSR entries; bit 2 = fp32 scores on the bf16 matrix cores, every fp32 operand split
+ * always through registers); bit 1 = L2SVM scores always by the dense contraction on the densified rows,
+ * bit 5 = always from the CSR entries where that kernel can take them (four rows of W in LDS: D <= 10240)
+ * (neither: whichever a fitted cost comparison on N, J, D and nnz expects to be faster); bit 2 = fp32 scores on the bf16 matrix cores, every fp32 operand split
  * exactly into three bf16 terms and every product taken as its six leading term products (error
  * at the level of one fp32 rounding; full batch and 16-byte aligned rows only, else ignored);
  * bit 3 = the same for the fp32 reconstruction (J, D multiples of 4, N a multiple of 32, no dead

@@ -74,7 +74,8 @@ struct sfb_ctx {
     size_t ws_bytes;
     int last_hip;
     bool timing;
-    bool sparse_forward;           // L2SVM: scores from the CSR entries when W rows fit in LDS
+    bool sparse_forward;           // L2SVM: scores from the CSR entries when W rows fit in LDS and that is the cheaper pass
+    bool sparse_always;            //   ... whenever they fit (no cost comparison)
     std::vector<EventPair> used[kFamilies], spare;
 };
 
@@ -225,7 +226,8 @@ sfb_status factors_rows(sfb_ctx* c, const FwdPlan& plan, const float* W, int64_t
             hipError_t e = launch_csr_densify(d, c->stream);
             if (e != hipSuccess) return hip_fail(c, e);
         }
-        if (c->sparse_forward && csr_scores_ok((int)c->D) && b->nnz <= (1LL << 30) - 1024) {
+        if (c->sparse_forward && csr_scores_ok((int)c->D) && b->nnz <= (1LL << 30) - 1024 &&
+            (c->sparse_always || csr_scores_wins(n_rows, c->J, c->D, b->nnz))) {
             // scores from the stored entries only: 2*nnz*J flops instead of 2*N*J*D
             Timed t(c, 0);
             hipError_t e = launch_csr_scores(d, W, ldw, (float*)c->ws, ldz, (int)c->J, c->stream);
@@ -360,7 +362,7 @@ sfb_status sfb_create(sfb_ctx** out, sfb_model m, int64_t J, int64_t D, int32_t 
     c->fused_ok = input_dtype == SFB_BF16 && m == SFB_MLR && fused_shape_ok(J, D, (int64_t)P * B);
     c->use_fused = true;
     c->fused = c->fused_ok ? plan_fused(J, D, (int64_t)P * B) : FusedPlan{};
-    c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->timing = false; c->sparse_forward = true;
+    c->ws = nullptr; c->ws_bytes = 0; c->last_hip = 0; c->timing = false; c->sparse_forward = true; c->sparse_always = false;
     // Set-up for sfb_step_noalloc on the device that is current now: resolve the address of the
     // library's scratch array, so that the entry point itself only reads it.  On a machine without a
     // GPU this fails; the context is still good for everything that can be checked on the host, and
@@ -686,6 +688,7 @@ sfb_status sfb_set_plan(sfb_ctx* c, int32_t fwd_bm, int32_t fwd_bn, int32_t fwd_
     if (fwd_split_k > 0) p.split_k = fwd_split_k;
     if (fwd_dma >= 0) p.dma = (fwd_dma & 1) != 0;
     if (fwd_dma >= 0) c->sparse_forward = (fwd_dma & 2) == 0;   // bit 1 set: dense scores for CSR input
+    if (fwd_dma >= 0) c->sparse_always = (fwd_dma & 32) != 0;   // bit 5 set: from the entries whenever the kernel can take them
     if (fwd_dma >= 0) c->split_scores = (fwd_dma & 4) != 0;     // bit 2 set: fp32 scores as split-bf16 products
     if (fwd_dma >= 0) c->split_recon = (fwd_dma & 8) != 0;      // bit 3 set: the reconstruction likewise
     if (fwd_dma >= 0) c->use_fused = (fwd_dma & 16) == 0;       // bit 4 set: sfb_step_pipelined runs two separate passes

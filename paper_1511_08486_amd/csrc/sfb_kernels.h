@@ -102,6 +102,8 @@ hipError_t launch_csr_densify(const DensifyArgs& a, hipStream_t s);
 // Scores straight from the CSR features (no dense A): Z[n][j] = sum_e val[e] * W[j][col[e]].
 // Usable when four W rows fit in LDS (csr_scores_ok); writes one slice (no split-K).
 bool csr_scores_ok(int D);
+// True when that pass is expected to beat the dense contraction on the densified rows (a fitted cost comparison).
+bool csr_scores_wins(int64_t n_rows, int64_t J, int64_t D, int64_t nnz);
 hipError_t launch_csr_scores(const DensifyArgs& a, const float* W, int64_t ldw, float* Z, int64_t ldz, int J,
                              hipStream_t s);
 

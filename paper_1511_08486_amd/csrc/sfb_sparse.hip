@@ -266,6 +266,27 @@ __global__ __launch_bounds__(kSpThreads) void csr_scores_kernel(
 bool csr_scores_ok(int D) { return (size_t)D * kSpRows * sizeof(float) <= 160 * 1024 - 1024; }
 // (the caller also needs nnz <= 2^30 - 1024: the kernel reads the CSR arrays through 32-bit byte offsets)
 
+// Which score pass is cheaper for this batch, in microseconds fitted to one MI355X (N = 256 and 1024, J = 16 to
+// 5000, D = 1024 to 10000, 2 % and 20 % stored).  From the entries: J / 4 workgroups, one per compute unit at a time,
+// each walks every row; a row costs about 20 ns plus 2 ns per 64-entry slab up to the three the kernel keeps in
+// flight and 19 ns per slab beyond, counted from 3.5 (long rows wait for their own loads and gathers).  Dense, on the densified
+// rows: the fp32 contraction at about 110 TFLOP/s on at least one 64-class block, and no faster than its walk
+// through D.  The entries win at the
+// benchmark's 2 % of 8192 columns with 2000 classes (66 against 283 us) and lose with few classes (J = 64: 30
+// against 13 us), short rows (D = 1024) or dense ones (20 %: 962 against 280 us).
+bool csr_scores_wins(int64_t n_rows, int64_t J, int64_t D, int64_t nnz) {
+    if (n_rows <= 0) return true;
+    double slabs = (double)((nnz / n_rows + 63) / 64);
+    if (slabs < 1.0) slabs = 1.0;
+    const double per_row = 0.020 + 0.0019 * (slabs < 3.0 ? slabs : 3.0) + 0.019 * (slabs > 3.5 ? slabs - 3.5 : 0.0);
+    const double rounds = (double)(((J + kSpRows - 1) / kSpRows + 255) / 256);
+    const double from_entries = 1.1 * rounds * (4.0 + (double)n_rows * per_row);
+    const double flops_us = 2.0 * (double)n_rows * (double)(J > 64 ? J : 64) * (double)D / 1.1e8;
+    const double walk_us = 0.0012 * (double)D;               // a small grid still walks its slices of D stage by stage
+    const double dense = 4.0 + (flops_us > walk_us ? flops_us : walk_us);
+    return from_entries < dense;
+}
+
 hipError_t launch_csr_scores(const DensifyArgs& a, const float* W, int64_t ldw, float* Z, int64_t ldz, int J,
                              hipStream_t s) {
     const size_t lds_bytes = (size_t)a.D * kSpRows * sizeof(float);

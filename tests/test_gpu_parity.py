@@ -266,7 +266,7 @@ def test_l2svm_ragged_and_empty_rows(sfb, dense_scores):
         keep = np.concatenate([np.arange(r * per, r * per + counts[r]) for r in range(wl.N)]).astype(np.int64)
         b["col"], b["val"] = b["col"][keep], b["val"][keep]
         b["rowptr"] = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
-    run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else None)
+    run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else dict(fwd_dma=33))
 
 
 def test_l2svm_rows_longer_than_the_score_kernel_prefetches(sfb):
@@ -283,7 +283,7 @@ def test_l2svm_rows_longer_than_the_score_kernel_prefetches(sfb):
         keep = np.concatenate([np.arange(r * per, r * per + counts[r]) for r in range(wl.N)]).astype(np.int64)
         b["col"], b["val"] = b["col"][keep], b["val"][keep]
         b["rowptr"] = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
-    run_chain(wl, 2, TOL32)
+    run_chain(wl, 2, TOL32, plan=dict(fwd_dma=33))          # from the entries, whatever the cost comparison says
 
 
 def test_l2svm_dense_score_fallback_full_size(sfb):
@@ -298,7 +298,7 @@ def test_l2svm_batch_with_no_stored_entries(sfb):
     b = wl.batch(0)
     b["col"], b["val"] = b["col"][:0], b["val"][:0]
     b["rowptr"] = np.zeros(wl.N + 1, dtype=np.int32)
-    for plan in (None, dict(fwd_dma=3)):
+    for plan in (None, dict(fwd_dma=33), dict(fwd_dma=3)):
         run_chain(wl, 1, TOL32, plan=plan)
 
 
@@ -631,8 +631,7 @@ def test_csr_worker_calls_address_the_shared_arrays_through_their_row_pointers(s
     wl = workloads.make("l2svm", seed=3, J=68, D=300, P=4, B=9, density=0.06, steps=1, pool=1)
     dev = "cuda:0"
     ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
-    if dense_scores:
-        ctx.set_plan(fwd_dma=3)
+    ctx.set_plan(fwd_dma=3 if dense_scores else 33)
     b = wl.batch(0)
     db, dy = to_device(wl, b, dev)
     W = torch.from_numpy(wl.W0).to(dev)
@@ -666,7 +665,7 @@ def test_csr_columns_in_any_order_within_a_row(sfb, dense_scores):
             b["col"][lo:hi] = b["col"][lo:hi][perm]
             b["val"][lo:hi] = b["val"][lo:hi][perm]
         assert np.any(np.diff(b["col"][:int(b["rowptr"][1])]) < 0)
-    run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else None)
+    run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else dict(fwd_dma=33))
 
 
 @pytest.mark.parametrize("dense_scores,D,density", [(False, 320, 0.05), (True, 320, 0.05), (False, 16500, 0.002)])
@@ -688,7 +687,7 @@ def test_csr_column_repeated_inside_a_row_counts_as_the_sum_of_its_values(sfb, d
             b["val"][lo:lo + per] = b["val"][lo:lo + per][perm]
         first = b["col"][:per]
         assert len(np.unique(first)) == per - 2
-    run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else None)
+    run_chain(wl, 2, TOL32, plan=dict(fwd_dma=3) if dense_scores else dict(fwd_dma=33))
 
 
 def _misaligned(t, off=1):
