@@ -113,7 +113,9 @@ SFB_API void sfb_destroy(sfb_ctx *ctx);
  * to 32 rows; the same bytes as the partial scores, which are dead by then): with it registered
  * their reconstruction runs the same matrix-core kernels as whole shapes, whatever the alignment
  * of U, V and W, without it the slower element-by-element kernel (same results to rounding).  A
- * call with a dead worker (`active`) likewise takes a masked copy of U in the partial scores' bytes.  The
+ * call with a dead worker (`active`) likewise takes a masked copy of U in the partial scores' bytes, and
+ * shapes of a few 64 x 64 tiles of W with thousands of factor pairs count planes of partial sums (the
+ * pairs are then cut into slices over workgroups and added in a fixed order).  The
  * caller allocates at least that many bytes, 256-byte aligned, and registers them; the library
  * uses the buffer until it is replaced or the ctx destroyed. */
 SFB_API sfb_status sfb_workspace_bytes(const sfb_ctx *ctx, size_t *bytes);

@@ -111,9 +111,15 @@ size_t workspace_need(const sfb_ctx* c) {
     if (c->fused_ok) need += fused_extra_workspace(c->D, (int64_t)c->P * c->B);   // staged next features, last
     // ragged fp32 shapes: padded copies of the factors, made and used inside one reconstruction, when the
     // partial scores (consumed by the factor kernel of the same call that wrote them) are dead: same bytes
+    // few tiles and many factor pairs: planes of partial sums behind those copies (or behind the masked copy of U)
     if (c->padded_factors) {
-        const size_t pad = conform_workspace(c->J, c->D, (int64_t)c->P * c->B);
+        const size_t pad = conform_workspace(c->J, c->D, (int64_t)c->P * c->B) +
+                           reconstruct_small_split_workspace(c->recon_padded.n_split, c->J, conform_cols(c->D));
         if (pad > need) need = pad;
+    } else if (c->dtype == SFB_F32 && c->recon.n_split > 1) {
+        const size_t sp = masked_workspace(c->J, (int64_t)c->P * c->B) +
+                          reconstruct_small_split_workspace(c->recon.n_split, c->J, c->D);
+        if (sp > need) need = sp;
     }
     // the column projection of the proximal step reuses the front of the buffer between steps
     const size_t prox = prox_workspace(c->J, c->D);
@@ -304,13 +310,24 @@ sfb_status recon_launch(sfb_ctx* c, float* W, int64_t ldw, const float* U, int64
         // kernels accept: padded ones for ragged shapes, U with a dead worker's rows zeroed for a masked call
         // (N x ceil4(J) floats: never more than the partial scores, whose bytes it takes)
         e = hipErrorNotSupported;
-        if (c->ws != nullptr && c->ws_bytes >= workspace_need(c) && !reconstruct_takes_dma(r, c->recon)) {
-            if (c->padded_factors && conformed_variant_ok(c->recon_padded.variant))
+        const bool have_ws = c->ws != nullptr && c->ws_bytes >= workspace_need(c);
+        const int64_t n_all = (int64_t)c->P * c->B;
+        if (have_ws && !reconstruct_takes_dma(r, c->recon)) {
+            if (c->padded_factors && conformed_variant_ok(c->recon_padded.variant)) {
+                if (c->recon_padded.n_split > 1) r.partial = (float*)((char*)c->ws + conform_workspace(c->J, c->D, n_all));
                 e = launch_reconstruct_conformed(r, c->recon_padded, c->ws, c->stream);
-            else if (r.use_mask && masked_workspace(c->J, r.N) <= scores_need(c))
+                r.partial = nullptr;
+            } else if (r.use_mask && masked_workspace(c->J, r.N) <= scores_need(c)) {
+                if (!c->padded_factors && c->recon.n_split > 1) r.partial = (float*)((char*)c->ws + masked_workspace(c->J, n_all));
                 e = launch_reconstruct_masked(r, c->recon, c->ws, c->stream);
+                r.partial = nullptr;
+            }
         }
-        if (e == hipErrorNotSupported) e = launch_reconstruct(r, c->recon, c->stream);
+        if (e == hipErrorNotSupported) {
+            if (have_ws && !c->padded_factors && c->recon.n_split > 1)
+                r.partial = (float*)((char*)c->ws + masked_workspace(c->J, n_all));
+            e = launch_reconstruct(r, c->recon, c->stream);
+        }
     }
     if (e != hipSuccess) return hip_fail(c, e);
     return SFB_OK;

@@ -137,6 +137,9 @@ struct ReconPlan {
     int variant;          // index into the tile table
     int bm, bn;           // W tile: rows (J) x columns (D)
     int grid;
+    // the single-block tiles with few tiles and many factor pairs: slices of the pairs over workgroups
+    // (sfb_reconstruct_small.hip); 1 = none.  Planned for n_rows pairs; calls with another count do not split.
+    int n_split = 1, k_rows = 0, n_rows = 0;
 };
 ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N);
 ReconPlan plan_reconstruct_variant(int64_t J, int64_t D, int variant);
@@ -159,6 +162,7 @@ struct ReconArgs {
     // alignment, any leading dimension, D columns.
     bool conformed = false;
     int Dp = 0;                    // columns of the padded v (a multiple of 128); 0: D itself
+    float* partial = nullptr;      // room for the plan's n_split planes of J x tile_cols() partial sums (256-byte aligned), or none
     int tile_cols() const { return Dp > 0 ? Dp : D; }
 };
 hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_t s);
@@ -186,6 +190,11 @@ hipError_t launch_reconstruct_masked(const ReconArgs& a, const ReconPlan& p, voi
 bool reconstruct_small_ok(const ReconArgs& a);
 bool reconstruct_small_wins(int64_t J, int64_t D, int big_bm, int big_waves);
 hipError_t launch_reconstruct_small(const ReconArgs& a, hipStream_t s);
+// the same tiles with the factor pairs cut into n_split slices of k_rows over workgroups and a second kernel that adds
+// the slices' sums in slice order (needs a.partial); reconstruct_small_split picks the count (1: do not split)
+int reconstruct_small_split(int64_t J, int64_t D, int64_t N, int* k_rows);
+size_t reconstruct_small_split_workspace(int n_split, int64_t J, int64_t D);
+hipError_t launch_reconstruct_small_split(const ReconArgs& a, int n_split, int k_rows, hipStream_t s);
 // (96..160) x 64 tiles whose eight wavefronts split the two column blocks, every stage's pairs and the stages
 // (sfb_reconstruct_ksplit.hip): for shapes where even single blocks leave the busiest SIMD well above the average
 bool reconstruct_ksplit_ok(const ReconArgs& a);

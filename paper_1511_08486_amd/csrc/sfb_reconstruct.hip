@@ -560,7 +560,6 @@ constexpr int kNumReconVariants = sizeof(kReconVariants) / sizeof(kReconVariants
 int num_reconstruct_variants() { return kNumReconVariants; }
 
 ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
-    (void)N;
     // largest tile that still gives every compute unit a workgroup; the smallest otherwise.
     // 7 and 8 are the LDS-DMA forms of the 128- and 64-row tiles (they fall back to the
     // register-staged kernel by themselves when the shape does not allow DMA).
@@ -601,7 +600,14 @@ ReconPlan plan_reconstruct(int64_t J, int64_t D, int64_t N) {
         // splitting the pairs as well where that evens the load out further (J = 600: 2.5 instead of 3)
         if (reconstruct_ksplit_wins(J, D, busiest)) variant = kKsplitVariant;
     }
-    return plan_reconstruct_variant(J, D, variant);
+    ReconPlan p = plan_reconstruct_variant(J, D, variant);
+    if (variant == kSmallVariant) {
+        // few tiles and many factor pairs: slices of the pairs over workgroups as well
+        p.n_split = reconstruct_small_split(J, D, N, &p.k_rows);
+        p.n_rows = (int)N;
+        p.grid *= p.n_split;
+    }
+    return p;
 }
 
 ReconPlan plan_reconstruct_variant(int64_t J, int64_t D, int variant) {
@@ -724,6 +730,7 @@ ReconPlan plan_reconstruct_padded(int64_t J, int64_t D, int64_t N, int variant) 
         const int rows = reconstruct_ksplit_rows(J);
         if (rows < 96 || rows > 160) v = kSmallVariant;      // what launch_reconstruct_conformed falls back to
     }
+    if (v == p.variant) return p;                            // (with the planner's slices of the pairs, if any)
     return plan_reconstruct_variant(J, dp, v);
 }
 
@@ -769,6 +776,8 @@ hipError_t launch_reconstruct_conformed(const ReconArgs& a, const ReconPlan& p, 
     if (e != hipSuccess) return e;
     if (variant == kPairVariant) return launch_reconstruct_pair(c, s);
     if (variant == kKsplitVariant) return launch_reconstruct_ksplit(c, s);
+    if (p.variant == kSmallVariant && p.n_split > 1 && c.partial != nullptr && c.N == p.n_rows)
+        return launch_reconstruct_small_split(c, p.n_split, p.k_rows, s);
     return launch_reconstruct_small(c, s);
 }
 
@@ -804,7 +813,11 @@ hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_
         q.variant = kSmallVariant;
     }
     if (q.variant == kSmallVariant) {
-        if (reconstruct_small_ok(a)) return launch_reconstruct_small(a, s);
+        if (reconstruct_small_ok(a)) {
+            if (p.variant == kSmallVariant && p.n_split > 1 && a.partial != nullptr && a.N == p.n_rows)
+                return launch_reconstruct_small_split(a, p.n_split, p.k_rows, s);
+            return launch_reconstruct_small(a, s);
+        }
         q.variant = 8;
     }
     if (kReconVariants[q.variant].dma) {

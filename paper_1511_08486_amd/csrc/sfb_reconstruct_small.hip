@@ -23,14 +23,20 @@ namespace sfb {
 
 constexpr int kRsmBM = 64, kRsmBN = 64, kRsmBK = 32, kRsmStages = 3, kRsmThreads = 256;
 
+// PARTIAL: the factor pairs are cut into slices of k_rows and the grid holds `tiles` workgroups per slice;
+// the workgroup of slice s contracts only its pairs and stores the bare sums (no alpha, no W, no proximal
+// operator) into plane s of W = the partial-sum planes [slice][J][ldw], which apply_partials_kernel then
+// adds up in slice order into the real W.
+template <bool PARTIAL>
 __global__ __launch_bounds__(kRsmThreads) void reconstruct_apply_small_kernel(
     float* __restrict__ W, int64_t ldw, const float* __restrict__ U, int64_t ldu, const float* __restrict__ V,
-    int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total, int prox_kind, float prox_a) {
+    int64_t ldv, int J, int D, int N, float alpha, int n_jb, int total, int prox_kind, float prox_a, int tiles,
+    int k_rows, int64_t pstride) {
     constexpr int BM = kRsmBM, BN = kRsmBN, BK = kRsmBK, NST = kRsmStages, THREADS = kRsmThreads;
     constexpr int U_LD = BK * BM / 4 / THREADS, V_LD = BK * BN / 4 / THREADS;      // 16-byte DMAs per thread and stage
     constexpr int DMAS = U_LD + V_LD;
     constexpr int STAGE_FLOATS = BK * (BM + BN);
-    constexpr int W_LOADS = 16;
+    constexpr int W_LOADS = PARTIAL ? 0 : 16;
     static_assert(U_LD == 2 && V_LD == 2, "tile / thread count mismatch");
     static_assert(NST == 3, "ring depth");
     static_assert(DMAS + W_LOADS <= 63, "wait count encoding");
@@ -39,7 +45,15 @@ __global__ __launch_bounds__(kRsmThreads) void reconstruct_apply_small_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int wr = wave >> 1, wc = wave & 1;                // this wavefront's 32 x 32 block of the tile
-    const int id = xcd_contiguous_id(blockIdx.x, total);
+    int id = xcd_contiguous_id(blockIdx.x, total);
+    if constexpr (PARTIAL) {
+        const int slice = id / tiles;                        // a die's workgroups share a slice's rows of U and V
+        id -= slice * tiles;
+        U += (int64_t)slice * k_rows * ldu;
+        V += (int64_t)slice * k_rows * ldv;
+        W += (int64_t)slice * pstride;
+        N = min(k_rows, N - slice * k_rows);                 // host: positive, a multiple of BK
+    }
     const int jb = id % n_jb, db = id / n_jb;
     const int j0 = jb * BM, d0 = db * BN;
 
@@ -118,10 +132,12 @@ __global__ __launch_bounds__(kRsmThreads) void reconstruct_apply_small_kernel(
     float wreg[16];
     const int col = d0 + wc * 32 + l32;                     // beyond D only in the last tile of padded factors
     const int colc = min(col, D - 1);
+    if constexpr (!PARTIAL) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        const int row = j0 + wr * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-        wreg[e] = W[(int64_t)min(row, J - 1) * ldw + colc];
+        for (int e = 0; e < 16; ++e) {
+            const int row = j0 + wr * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+            wreg[e] = W[(int64_t)min(row, J - 1) * ldw + colc];
+        }
     }
     int st = 1;
     for (int c = 1; c < n_chunks; ++c) {
@@ -132,7 +148,11 @@ __global__ __launch_bounds__(kRsmThreads) void reconstruct_apply_small_kernel(
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
         const int row = j0 + wr * 32 + 8 * (e / 4) + 4 * half + (e % 4);
-        if (row < J && col < D) W[(int64_t)row * ldw + col] = prox_entry(wreg[e] + alpha * acc[e], prox_kind, prox_a);
+        if constexpr (PARTIAL) {
+            if (row < J) W[(int64_t)row * ldw + col] = acc[e];          // a plane holds whole column tiles
+        } else {
+            if (row < J && col < D) W[(int64_t)row * ldw + col] = prox_entry(wreg[e] + alpha * acc[e], prox_kind, prox_a);
+        }
     }
 }
 
@@ -162,8 +182,74 @@ bool reconstruct_small_wins(int64_t J, int64_t D, int big_bm, int big_waves) {
 hipError_t launch_reconstruct_small(const ReconArgs& a, hipStream_t s) {
     const int n_jb = (a.J + kRsmBM - 1) / kRsmBM, n_db = a.tile_cols() / kRsmBN;
     const int total = n_jb * n_db;
-    SFB_LAUNCH(reconstruct_apply_small_kernel, dim3(total), dim3(kRsmThreads), 0, s, a.w, a.ldw, a.u, a.ldu,
-               (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total, a.prox_kind, a.prox_a);
+    SFB_LAUNCH(reconstruct_apply_small_kernel<false>, dim3(total), dim3(kRsmThreads), 0, s, a.w, a.ldw, a.u, a.ldu,
+               (const float*)a.v, a.ldv, a.J, a.D, a.N, a.alpha, n_jb, total, a.prox_kind, a.prox_a, total, 0,
+               (int64_t)0);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Few tiles, many factor pairs (ten classes x 784 features with 12000 pairs: 14 tiles, 375 stages):
+// one workgroup per tile leaves most of the chip idle for a long walk.  The pairs are cut into
+// n_split slices, tiles x n_split workgroups store their slice's bare sums into planes of the
+// workspace, and one streaming kernel adds the planes in slice order -- a fixed order, so results do
+// not depend on timing -- scales by alpha, adds W and applies the proximal operator.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void apply_partials_kernel(float* __restrict__ W, int64_t ldw,
+                                                             const float* __restrict__ P, int64_t ldp, int64_t pstride,
+                                                             int n_split, int J, int D, float alpha, int n_cb,
+                                                             int prox_kind, float prox_a) {
+    const int row = blockIdx.x / n_cb, col = (blockIdx.x % n_cb) * 256 + threadIdx.x;
+    if (row >= J || col >= D) return;
+    const float* p = P + (int64_t)row * ldp + col;
+    float sum = 0.f;
+    for (int k = 0; k < n_split; ++k) sum += p[(int64_t)k * pstride];
+    float* w = W + (int64_t)row * ldw + col;
+    *w = prox_entry(*w + alpha * sum, prox_kind, prox_a);
+}
+
+// Slices of the pairs for a (J, D, N) whose plan is the single-block tile: the count that minimises, in
+// microseconds, max(latency of one workgroup's walk, the busiest compute unit's share of all walks) + the
+// adding-up pass.  A stage of 32 pairs takes a lone wavefront per SIMD about 0.67 us, and a compute unit
+// turns over one workgroup-stage per 0.49 us when several workgroups share it.  1: do not split.
+int reconstruct_small_split(int64_t J, int64_t D, int64_t N, int* k_rows) {
+    *k_rows = 0;
+    if ((D % kRsmBN) != 0 || (N % kRsmBK) != 0) return 1;
+    const int64_t tiles = ((J + kRsmBM - 1) / kRsmBM) * (D / kRsmBN), chunks = N / kRsmBK;
+    int64_t best = 1;
+    double best_cost = 1e300, whole_cost = 1e300;
+    for (int64_t s = 1; s <= 32 && (s == 1 || chunks / s >= 4); ++s) {
+        const int64_t per = (chunks + s - 1) / s;
+        if ((chunks + per - 1) / per != s) continue;                          // the same cut as a smaller count
+        if (s > 1 && s * J * D * 4 > (64LL << 20)) break;                     // planes of partial sums: 64 MB at most
+        const double latency = (double)per * 0.67;
+        const double share = (double)((tiles * s + 255) / 256) * (double)per * 0.49;
+        double cost = (latency > share ? latency : share) + 6.0;
+        if (s > 1) cost += 6.0 + ((double)s * (double)J * (double)D * 4.0 + (double)J * (double)D * 8.0) / 4e6;
+        if (s == 1) whole_cost = cost;
+        else if (cost < best_cost * 0.95) { best_cost = cost; best = s; }     // a further slice must buy 5 %
+    }
+    if (best == 1 || best_cost > 0.8 * whole_cost) return 1;                  // and splitting at all 20 %
+    *k_rows = (int)((chunks + best - 1) / best * kRsmBK);
+    return (int)best;
+}
+
+size_t reconstruct_small_split_workspace(int n_split, int64_t J, int64_t D) {
+    return n_split > 1 ? ((size_t)n_split * (size_t)J * (size_t)D * sizeof(float) + 255) / 256 * 256 : 0;
+}
+
+// a.partial: n_split planes of J x a.tile_cols() floats, 256-byte aligned.
+hipError_t launch_reconstruct_small_split(const ReconArgs& a, int n_split, int k_rows, hipStream_t s) {
+    const int n_jb = (a.J + kRsmBM - 1) / kRsmBM, n_db = a.tile_cols() / kRsmBN;
+    const int tiles = n_jb * n_db, total = tiles * n_split;
+    const int64_t ldp = a.tile_cols(), pstride = (int64_t)a.J * ldp;
+    SFB_LAUNCH(reconstruct_apply_small_kernel<true>, dim3(total), dim3(kRsmThreads), 0, s, a.partial, ldp, a.u, a.ldu,
+               (const float*)a.v, a.ldv, a.J, a.D, a.N, 1.0f, n_jb, total, 0, 0.f, tiles, k_rows, pstride);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int n_cb = (a.D + 255) / 256;
+    hipLaunchKernelGGL(apply_partials_kernel, dim3(a.J * n_cb), dim3(256), 0, s, a.w, a.ldw, a.partial, ldp, pstride,
+                       n_split, a.J, a.D, a.alpha, n_cb, a.prox_kind, a.prox_a);
     return hipGetLastError();
 }
 

@@ -155,6 +155,45 @@ def test_a_dead_worker_in_a_whole_shape_goes_through_a_masked_copy_of_u(sfb):
     ctx.close()
 
 
+@pytest.mark.parametrize("name,over,tiles", [
+    ("mlr_tiny", dict(J=10, D=784, P=12, B=100), 14),        # ragged: padded copies, then slices of their 1216 rows
+    ("mlr_tiny", dict(J=64, D=128, P=16, B=128), 2),         # whole: two tiles, 64 stages
+    ("dml", dict(J=100, D=192, P=8, B=256), 8),              # 192 -> 256 columns: 2 x 4 tiles
+    ("l2svm", dict(J=48, D=320, P=4, B=300, density=0.05), 6),   # 320 -> 384 columns
+])
+def test_few_tiles_many_pairs_split_the_pairs_over_workgroups(sfb, name, over, tiles):
+    """J x D of a few 64 x 64 tiles with thousands of factor pairs: the plan cuts the pairs into slices, one
+    workgroup per tile and slice stores bare sums, a second kernel adds them in slice order.  Two steps against
+    the oracle, the same call twice bit for bit, and with a dead worker."""
+    wl = make_clear_of_kink(name, 91, 2, steps=2, pool=2, **over)
+    dev = "cuda:0"
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+    grid = ctx.plan_info()["recon_grid"]
+    assert grid % tiles == 0 and grid // tiles > 1, f"the plan does not split: {grid} workgroups for {tiles} tiles"
+    ctx.close()
+    run_chain(wl, 2, TOL32, pad=0)
+    # determinism and the mask, on the reconstruction alone
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+    rng = np.random.default_rng(3)
+    Uh = rng.standard_normal((wl.N, wl.J)).astype(np.float32)
+    Vh = rng.standard_normal((wl.N, wl.D)).astype(np.float32)
+    active = [1] * wl.P
+    active[1] = 0
+    for mask in (None, active):
+        got = []
+        for _ in range(2):
+            W = torch.from_numpy(wl.W0).to(dev)
+            ctx.reconstruct_apply(W, torch.from_numpy(Uh).to(dev), torch.from_numpy(Vh).to(dev), wl.eta, active=mask)
+            ctx.sync()
+            got.append(W)
+        assert torch.equal(got[0], got[1])
+        dW = oracle.delta_w(Uh, Vh, wl.P, wl.B, active=mask)
+        mag = wl.eta * oracle.delta_w(np.abs(Uh), np.abs(Vh), wl.P, wl.B, active=mask)
+        assert_close(got[0].cpu().numpy(), oracle.apply_update(wl.W0.astype(np.float64), dW, wl.eta), TOL32,
+                     f"W, mask {mask}", terms=mag)
+    ctx.close()
+
+
 def test_mlr_medium_hundred_steps(sfb):
     wl = workloads.make("mlr_medium")
     worst = run_chain(wl, wl.steps, TOL32, check_every=7)
