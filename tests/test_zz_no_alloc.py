@@ -33,6 +33,8 @@ def _both(sfb, name, over, dev="cuda:0"):
     (("mlr_medium", dict()), ("mlr_medium", dict(J=200, D=520, P=3, B=24))),            # 8.2 MB of scratch, then 58 KB
     (("dml", dict(J=300, D=1024, P=4, B=64)), ("l2svm", dict(J=68, D=300, P=2, B=9, density=0.06))),
     (("mlr_large", dict(J=1000, D=2048, P=4, B=64)), ("mlr_large", dict(J=300, D=1024, P=4, B=40))),   # bf16: packed factors too
+    # padded factor copies and planes of partial sums (few tiles, many pairs) in the scratch, then a whole shape with planes
+    (("mlr_tiny", dict(J=10, D=784, P=12, B=100)), ("mlr_tiny", dict(J=64, D=128, P=16, B=128))),
 ])
 def test_noalloc_step_equals_step_on_two_calls_in_a_row(first, second):
     import paper_1511_08486_amd as sfb
