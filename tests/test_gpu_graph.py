@@ -13,7 +13,9 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("name,over", [("mlr_tiny", {}), ("mlr_medium", dict(J=200, D=512, P=4, B=32)),
                                        ("dml", dict(J=96, D=256, P=2, B=64)),
-                                       ("l2svm", dict(J=64, D=512, P=2, B=32))])
+                                       ("l2svm", dict(J=64, D=512, P=2, B=32)),
+                                       # padded factor copies, slices of the pairs over workgroups, the adding-up kernel
+                                       ("mlr_tiny", dict(J=10, D=784, P=12, B=100))])
 def test_step_recorded_in_a_graph_replays_like_eager_steps(name, over):
     import paper_1511_08486_amd as sfb
     dev = "cuda:0"
