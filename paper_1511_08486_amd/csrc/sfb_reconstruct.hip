@@ -788,6 +788,11 @@ bool reconstruct_takes_dma(const ReconArgs& a, const ReconPlan& p) {
     if (a.bf16 || !kReconVariants[v].dma) return false;
     if (v == kPairVariant) {
         if (reconstruct_pair_ok(a)) return true;
+        if (!a.conformed && (a.J % 4) == 0 && a.J >= 4) {     // W alone off the 16-byte grid
+            ReconArgs c = a;
+            c.conformed = true;
+            if (reconstruct_pair_ok(c)) return true;
+        }
         v = 7;
     }
     if (v == kKsplitVariant) {
@@ -806,6 +811,13 @@ hipError_t launch_reconstruct(const ReconArgs& a, const ReconPlan& p, hipStream_
     ReconPlan q = p;
     if (p.variant == kPairVariant) {
         if (reconstruct_pair_ok(a)) return launch_reconstruct_pair(a, s);
+        // whole, aligned factors and only W off the 16-byte grid (or with a leading dimension that is not a
+        // multiple of 4): the same kernel in the form that takes W entry by entry
+        if (!a.conformed && (a.J % 4) == 0 && a.J >= 4) {
+            ReconArgs c = a;
+            c.conformed = true;
+            if (reconstruct_pair_ok(c)) return launch_reconstruct_pair(c, s);
+        }
         q.variant = 7;
     }
     if (p.variant == kKsplitVariant) {

@@ -194,6 +194,31 @@ def test_few_tiles_many_pairs_split_the_pairs_over_workgroups(sfb, name, over, t
     ctx.close()
 
 
+def test_w_alone_off_the_16_byte_grid_keeps_the_pair_kernel(sfb):
+    """Whole shape with 256 tiles of 128 x 128 (the pair kernel's plan), aligned U and V, and a W whose leading
+    dimension is D + 1: the reconstruction takes W entry by entry instead of falling back to register staging.
+    Checked against the oracle on the update itself."""
+    dev = "cuda:0"
+    J, D, P, B, eta = 2048, 2048, 2, 32, 0.1
+    N = P * B
+    rng = np.random.default_rng(17)
+    W0 = (0.1 * rng.standard_normal((J, D))).astype(np.float32)
+    Uh = rng.standard_normal((N, J)).astype(np.float32)
+    Vh = rng.standard_normal((N, D)).astype(np.float32)
+    ctx = sfb.Sfb("mlr", J, D, P, B, device=dev)
+    assert ctx.plan_info()["recon_grid"] == 256
+    Wbuf = torch.full((J, D + 1), 7.0, dtype=torch.float32, device=dev)
+    W = Wbuf[:, :D]
+    W.copy_(torch.from_numpy(W0))
+    ctx.reconstruct_apply(W, torch.from_numpy(Uh).to(dev), torch.from_numpy(Vh).to(dev), eta)
+    ctx.sync()
+    dW = oracle.delta_w(Uh, Vh, P, B)
+    mag = eta * oracle.delta_w(np.abs(Uh), np.abs(Vh), P, B)
+    assert_close(W.cpu().numpy(), oracle.apply_update(W0.astype(np.float64), dW, eta), TOL32, "W", terms=mag)
+    assert bool((Wbuf[:, D] == 7.0).all())                               # the column beyond D is not W's
+    ctx.close()
+
+
 def test_mlr_medium_hundred_steps(sfb):
     wl = workloads.make("mlr_medium")
     worst = run_chain(wl, wl.steps, TOL32, check_every=7)
