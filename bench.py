@@ -80,6 +80,25 @@ def stage_pool(wl, sfb, torch, dev):
     return pool, vdt
 
 
+SETTLE_S = 0.3
+
+
+def settle(run, restore, torch, chunk):
+    """Untimed: keeps the step loop running for SETTLE_S seconds (W restored every `chunk` steps) and returns the
+    number of steps run.  The device needs tens of milliseconds of sustained load before its dispatch path reaches
+    its steady rate: straight after the W warm-up steps asked for (0.5 ms of work at mlr_medium) a 20-step repeat reads
+    9 % above the same repeat taken after this loop (2 % at mlr_large), and any run of a few thousand steps is in the
+    steady state.  The timed regions are untouched: exactly `steps` steps between two synchronisations."""
+    done = 0
+    t_end = time.perf_counter() + SETTLE_S
+    while time.perf_counter() < t_end:
+        restore()
+        run(chunk)
+        torch.cuda.synchronize()
+        done += chunk
+    return done
+
+
 def timed_repeats(run, restore, torch, steps, repeats=REPEATS):
     """`repeats` times: restore W, synchronise, time exactly `steps` steps, synchronise."""
     out = []
@@ -196,6 +215,7 @@ def bench_config(name, args, sfb, torch, workloads, traffic_table, cpu_seconds, 
         steps = max(len(pool), steps // len(pool) * len(pool))
         run(warmup)
 
+    settled = settle(run, lambda: W.copy_(W0), torch, max(warmup, len(pool)))
     times = timed_repeats(run, lambda: W.copy_(W0), torch, steps)
     assert bool(torch.isfinite(W).all()), "W is not finite after the timed steps"
     med, best = statistics.median(times), min(times)
@@ -222,7 +242,10 @@ def bench_config(name, args, sfb, torch, workloads, traffic_table, cpu_seconds, 
         "steps_per_sec": steps / med,
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": med / steps * 1e3,
         "ms_per_step_min": best / steps * 1e3, "repeats_ms_per_step": [round(t / steps * 1e3, 6) for t in times],
-        "timing": f"median of {REPEATS} repeats of {steps} steps, W restored to W0 before each",
+        "timing": f"median of {REPEATS} repeats of {steps} steps, W restored to W0 before each; before them, untimed, "
+                  f"{warmup} warm-up steps and {settled} more over {SETTLE_S} s (the device's dispatch path needs "
+                  f"tens of ms of load to reach its steady rate)",
+        "warmup_settle_steps": settled,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl.dtype == "f32" else "bf16 features, f32 accumulate",
         "data": "synthetic",
