@@ -219,6 +219,29 @@ def test_w_alone_off_the_16_byte_grid_keeps_the_pair_kernel(sfb):
     ctx.close()
 
 
+def test_scores_far_beyond_the_range_of_exp_do_not_overflow(sfb):
+    """Scores of +-150 and more (exp overflows fp32 beyond 88.7): the factor kernel subtracts the row maximum, so
+    u = softmax - e_y and the loss stay finite and match the oracle.  The bar is 1e-2 here: an fp32 score of
+    magnitude 150 carries an absolute error of 1e-5 to 1e-4, which the softmax turns into that relative error of
+    a probability, so the 1e-4 bar of the other tests does not apply to this input."""
+    dev = "cuda:0"
+    wl = workloads.make("mlr_tiny", seed=13, J=40, D=64, P=4, B=32, steps=1, pool=1)
+    W0 = (wl.W0 * 2000.0).astype(np.float32)
+    b = wl.batch(0)
+    Z = oracle.scores(W0.astype(np.float64), b["A"].astype(np.float64))
+    assert np.abs(Z).max() > 150.0
+    ctx = sfb.Sfb(wl.model, wl.J, wl.D, wl.P, wl.B, device=dev)
+    db, dy = to_device(wl, b, dev)
+    U, V, loss = alloc_factors(wl, dev)
+    ctx.compute_factors(torch.from_numpy(W0).to(dev), db, dy, U, V, loss)
+    ctx.sync()
+    assert bool(torch.isfinite(U).all()) and bool(torch.isfinite(loss).all())
+    Uo, Vo, _, fo = oracle.step(wl.model, W0.astype(np.float64), b, wl.P, wl.B, wl.eta)
+    assert_close(U.cpu().numpy(), Uo, 1e-2, "U")
+    assert_close(loss.cpu().numpy(), fo, 1e-4, "loss")       # the loss is a difference of scores: no such amplification
+    ctx.close()
+
+
 def test_mlr_medium_hundred_steps(sfb):
     wl = workloads.make("mlr_medium")
     worst = run_chain(wl, wl.steps, TOL32, check_every=7)
